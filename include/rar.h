@@ -1,0 +1,168 @@
+/*
+ * rar.h - C ABI of the MI355X (gfx950) hierarchical recursive-doubling all-reduce.
+ *
+ * The operation is the three-phase all-reduce of the paper's Algorithm 1 ("NVRAR") and
+ * Section 4.1: an intra-node reduce-scatter over the G ranks of a node, log2(N) inter-node
+ * recursive-doubling exchange-and-sum steps on each rank's 1/G chunk (step l pairs rank
+ * (r_n, r_g) with rank (r_n XOR 2^l, r_g)), then an intra-node all-gather.  All P = G*N
+ * ranks are emulated on ONE GPU as P resident device buffers; rank p = r_n*G + r_g.
+ *
+ * Numerics (fixed, the result is a function of the schedule): elements are widened to
+ * binary32, added with round-to-nearest-even and gradual underflow; the reduce-scatter adds
+ * local ranks 0..G-1 in that order in binary32 and narrows once to the message type; every
+ * inter-node step narrows its sum to the message type; bf16 narrowing rounds to nearest,
+ * ties to even.  NaN results are NaN, their payload is unspecified.
+ *
+ * Conventions
+ *   - "host" / "device" is stated for every pointer.  Device pointers are plain addresses in
+ *     the current HIP device's memory (e.g. torch.Tensor.data_ptr()).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls that take
+ *     a stream only enqueue work and return; results are valid in stream order.
+ *   - Every function returns RAR_OK (0) or a negative rar_status.  No exceptions, no aborts.
+ *   - Nothing here allocates or frees device memory; scratch is lent by the caller.
+ *   - A plan is not thread-safe, and two all-reduces on one plan must not overlap in time
+ *     (they share the plan's scratch): order them on one stream or use two plans.
+ */
+#ifndef RAR_H
+#define RAR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum rar_dtype {
+    RAR_BF16 = 0, /* 2-byte bfloat16 (upper half of binary32) */
+    RAR_F32 = 1   /* 4-byte IEEE binary32 */
+} rar_dtype;
+
+typedef enum rar_mode {
+    RAR_MODE_STEPWISE = 0, /* one launch per phase: 1 reduce-scatter + L steps + 1 all-gather */
+    RAR_MODE_FUSED = 1     /* one persistent launch; flag-based step barriers (default)      */
+} rar_mode;
+
+typedef enum rar_status {
+    RAR_OK = 0,
+    RAR_ERR_ARG = -1,     /* NULL pointer, P < 1, G < 1, n == 0, value out of range        */
+    RAR_ERR_SHAPE = -2,   /* G does not divide P, or N = P/G is not a power of two          */
+    RAR_ERR_DTYPE = -3,   /* unknown rar_dtype                                              */
+    RAR_ERR_LIMIT = -4,   /* P > RAR_MAX_RANKS or n too large for 32-bit vector indices     */
+    RAR_ERR_SCRATCH = -5, /* scratch not set, too small, or misaligned                      */
+    RAR_ERR_ALIGN = -6,   /* a data pointer is not 16-byte aligned                          */
+    RAR_ERR_HIP = -7,     /* a HIP call failed (no device, launch error, ...)               */
+    RAR_ERR_TIMEOUT = -8, /* a step barrier gave up waiting (reported by rar_plan_status)   */
+    RAR_ERR_TUNING = -9   /* rar_plan_set_tuning: unsupported B_s / C_s                     */
+} rar_status;
+
+#define RAR_MAX_RANKS 128
+
+typedef struct rar_plan_s rar_plan_t;
+
+/* Library version, major*10000 + minor*100 + patch. */
+int rar_version(void);
+
+/* Static, never-NULL description of a status code. */
+const char *rar_strerror(int status);
+
+/* ---- planner (host only; Algorithm 1's inputs G, N, C_s and its peer rule) ---------------
+ *
+ * rar_plan: build the schedule for P ranks, G per node, n elements of `dtype` per rank.
+ *   N = P/G nodes, L = log2 N steps.  The message is cut into G chunks: chunk length is
+ *   ceil(n/G) rounded up to whole 16-byte groups, chunk c covers elements
+ *   [min(c*len, n), min((c+1)*len, n)), so trailing chunks may be short or empty (the paper
+ *   writes |M|/G and does not treat the ragged case).  N = 1 (no inter-node phase) and G = 1
+ *   (phases 1 and 3 reduce to a copy) are valid.  N that is not a power of two is rejected:
+ *   the algorithm has no rule for it.
+ *   *out (host) receives a plan owned by the caller; release it with rar_plan_free.
+ *   Touches no device.
+ */
+int rar_plan(int P, int G, size_t n, int dtype, rar_plan_t **out);
+int rar_plan_free(rar_plan_t *plan);
+
+/* Shape queries (host only). rar_plan_steps returns L; rar_plan_nodes returns N. */
+int rar_plan_ranks(const rar_plan_t *plan);
+int rar_plan_nodes(const rar_plan_t *plan);
+int rar_plan_steps(const rar_plan_t *plan);
+
+/* Peer of `rank` at inter-node step `step` (0 <= step < L): (r_n XOR 2^step)*G + r_g
+ * (Algorithm 1, peer rule of RD_inter).  Negative rar_status on bad arguments. */
+int rar_plan_peer(const rar_plan_t *plan, int rank, int step);
+
+/* Element range of chunk c (0 <= c < G): *offset and *length (host, both required). */
+int rar_plan_chunk(const rar_plan_t *plan, int c, size_t *offset, size_t *length);
+
+/* Bytes of device scratch rar_allreduce needs: a 256-byte header (status word), the step
+ * barrier flags, and the per-step partial buffers S_0..S_L of every rank (Section 4.2.1:
+ * one buffer per inter-node step, so a rank may run ahead of its peer). */
+size_t rar_plan_scratch_bytes(const rar_plan_t *plan);
+
+/* Lend `bytes` of device memory at `scratch` (256-byte aligned, >= rar_plan_scratch_bytes)
+ * to the plan.  The plan borrows it until rar_plan_free or the next set_scratch; the caller
+ * frees it afterwards.  Contents need no initialisation: the first all-reduce clears the
+ * header and flags with a fill kernel on its stream. */
+int rar_plan_set_scratch(rar_plan_t *plan, void *scratch, size_t bytes);
+
+/* Execution mode (default RAR_MODE_FUSED).  Both modes produce identical bits. */
+int rar_plan_set_mode(rar_plan_t *plan, int mode);
+int rar_plan_get_mode(const rar_plan_t *plan);
+
+/* The paper's two hyper-parameters (Section 4.2.1, Appendix "Impact of Chunk Size and Block
+ * Size"): B_s = workgroups per rank, C_s = bytes of a rank's chunk that one workgroup moves
+ * per trip (its "chunk" of the chunked pipeline).  C_s must be 4096, 8192, 16384 or 32768;
+ * 1 <= B_s <= 256.  B_s = 0 and/or C_s = 0 restore the built-in choice for that parameter.
+ * They change timing only, never a result bit.  In fused mode B_s is clamped at launch so
+ * that all P*B_s workgroups are resident at once (the step barriers need that). */
+int rar_plan_set_tuning(rar_plan_t *plan, int B_s, size_t C_s);
+int rar_plan_get_tuning(const rar_plan_t *plan, int *B_s, size_t *C_s);
+
+/* Upper bound on the time one step-barrier wait may take before the kernel gives up, in
+ * microseconds (default 5,000,000).  A wait that gives up records RAR_ERR_TIMEOUT in the
+ * scratch header, and every workgroup still runs to the end of the kernel (no hang); the
+ * output buffers are then unspecified. */
+int rar_plan_set_wait_limit_us(rar_plan_t *plan, uint64_t microseconds);
+
+/* Synchronise `stream`, read the status word of the scratch header and return it
+ * (RAR_OK or RAR_ERR_TIMEOUT), clearing it and scheduling a flag reset if it was set. */
+int rar_plan_status(rar_plan_t *plan, void *stream);
+
+/* ---- one rank's exchange-and-sum (Algorithm 1, RD_inter: B_send[l+1] <- dst + src) --------
+ *
+ * For i in [chunk*n, chunk*n + n):  dst[i] <- narrow( widen(dst[i]) + widen(src[i]) ).
+ * dst, src: device base pointers of two buffers with identical layout, 16-byte aligned,
+ * not overlapping; n = elements per chunk, chunk = chunk index, so the touched byte offset
+ * chunk*n*sizeof(element) must itself be a multiple of 16.  dtype is a rar_dtype (the
+ * paper's list of arguments has no type because its buffers are typed by the call site).
+ * Enqueues one kernel on `stream`; src must not be written while it runs.  n == 0 is a
+ * no-op.
+ */
+int rar_step_combine(void *dst, const void *src, size_t chunk, size_t n, int dtype, void *stream);
+
+/* ---- the whole schedule (Algorithm 1, function NVRAR) --------------------------------------
+ *
+ * bufs: host array of P device pointers; bufs[p] is rank p's message M of n elements,
+ * 16-byte aligned, the P buffers pairwise disjoint and disjoint from the scratch.  The array
+ * is read before the call returns.  In place: once the enqueued work has run, every buffer
+ * holds the schedule-ordered sum, the same bits on all ranks.  Fused mode is one launch
+ * (plus a fill launch on a plan's first use); stepwise mode is L + 2 launches.
+ */
+int rar_allreduce(void *const *bufs, rar_plan_t *plan, void *stream);
+
+/* ---- measurement aids (used by the benchmark, no effect on results) -----------------------
+ *
+ * rar_launch_floor: enqueue an empty kernel with the grid and block size the plan's fused
+ *   all-reduce would use (the single-launch floor).
+ * rar_barrier_only: enqueue the fused kernel with all data movement left out: only the step
+ *   barrier traffic (flag stores, waits, fences) of a real call.
+ * rar_copy_probe: enqueue a plain 16-byte-vector copy of `bytes` bytes (multiple of 16)
+ *   from src to dst (device), the known-size kernel that rocprof counters are scaled by.
+ */
+int rar_launch_floor(rar_plan_t *plan, void *stream);
+int rar_barrier_only(rar_plan_t *plan, void *stream);
+int rar_copy_probe(void *dst, const void *src, size_t bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RAR_H */

@@ -1,0 +1,133 @@
+// Device-touching part of the C ABI (include/rar.h): argument checks on the host, then
+// launches.  Every shape the kernels assume is verified here before anything is enqueued.
+#include <hip/hip_runtime.h>
+
+#include <cstring>
+
+#include "launch.hpp"
+
+using rar::Geometry;
+using rar::RankPtrs;
+using rar::Tuning;
+
+namespace {
+
+inline hipStream_t as_stream(void *s) { return static_cast<hipStream_t>(s); }
+
+int ensure_scratch(const rar_plan_t *plan) {
+    if (!plan->scratch || plan->scratch_size < plan->geo.scratch_bytes) return RAR_ERR_SCRATCH;
+    return RAR_OK;
+}
+
+// Zero the header and the barrier flags on the stream if they are not known to be clean.
+int ensure_flags(rar_plan_t *plan, hipStream_t stream) {
+    if (plan->flags_clean) return RAR_OK;
+    int rc = rar::launch_fill_zero(plan->scratch, plan->geo.data_offset, stream);
+    if (rc == RAR_OK) plan->flags_clean = true;
+    return rc;
+}
+
+int ensure_residency(rar_plan_t *plan) {
+    if (plan->have_resident) return RAR_OK;
+    for (int i = 0; i < 4; ++i) {
+        int rc = rar::fused_max_resident(plan->geo.dtype, plan->geo.G, 1 << i, &plan->resident[i]);
+        if (rc != RAR_OK) return rc;
+    }
+    plan->have_resident = true;
+    return RAR_OK;
+}
+
+// The fused kernel's step barriers need every workgroup of the grid resident at once.
+int fused_tuning(rar_plan_t *plan, Tuning *t) {
+    int rc = ensure_residency(plan);
+    if (rc != RAR_OK) return rc;
+    *t = rar::resolve_tuning(*plan, plan->resident);
+    const int index = t->unroll == 1 ? 0 : t->unroll == 2 ? 1 : t->unroll == 4 ? 2 : 3;
+    if (static_cast<long>(plan->geo.P) * t->B_s > plan->resident[index]) return RAR_ERR_LIMIT;
+    return RAR_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int rar_plan_status(rar_plan_t *plan, void *stream) {
+    if (!plan) return RAR_ERR_ARG;
+    if (ensure_scratch(plan) != RAR_OK) return RAR_ERR_SCRATCH;
+    if (hipStreamSynchronize(as_stream(stream)) != hipSuccess) return RAR_ERR_HIP;
+    if (!plan->flags_clean) return RAR_OK;  // header never initialised: nothing has run
+    uint32_t word = 0;
+    if (hipMemcpy(&word, plan->scratch, sizeof word, hipMemcpyDeviceToHost) != hipSuccess) return RAR_ERR_HIP;
+    if (word == 0) return RAR_OK;
+    plan->flags_clean = false;  // counters of different slots may now disagree: start over
+    return RAR_ERR_TIMEOUT;
+}
+
+int rar_step_combine(void *dst, const void *src, size_t chunk, size_t n, int dtype, void *stream) {
+    if (!dst || !src) return RAR_ERR_ARG;
+    if (dtype != RAR_BF16 && dtype != RAR_F32) return RAR_ERR_DTYPE;
+    if (n == 0) return RAR_OK;
+    const size_t es = dtype == RAR_BF16 ? 2 : 4;
+    if (chunk != 0 && n > SIZE_MAX / es / chunk) return RAR_ERR_LIMIT;
+    const size_t offset = chunk * n * es;
+    if ((reinterpret_cast<uintptr_t>(dst) | reinterpret_cast<uintptr_t>(src) | offset) % 16 != 0) return RAR_ERR_ALIGN;
+    const size_t per_vec = 16 / es;
+    unsigned char *d = static_cast<unsigned char *>(dst) + offset;
+    const unsigned char *s = static_cast<const unsigned char *>(src) + offset;
+    const size_t bytes = n * es;
+    if ((d < s + bytes) && (s < d + bytes)) return RAR_ERR_ARG;  // overlapping ranges
+    return rar::launch_combine(d, s, n / per_vec, static_cast<unsigned>(n % per_vec), dtype, as_stream(stream));
+}
+
+int rar_allreduce(void *const *bufs, rar_plan_t *plan, void *stream) {
+    if (!bufs || !plan) return RAR_ERR_ARG;
+    const Geometry &g = plan->geo;
+    int rc = ensure_scratch(plan);
+    if (rc != RAR_OK) return rc;
+    RankPtrs ptrs;
+    std::memset(&ptrs, 0, sizeof ptrs);
+    for (int p = 0; p < g.P; ++p) {
+        if (!bufs[p]) return RAR_ERR_ARG;
+        if (reinterpret_cast<uintptr_t>(bufs[p]) % 16 != 0) return RAR_ERR_ALIGN;
+        ptrs.p[p] = bufs[p];
+    }
+    hipStream_t st = as_stream(stream);
+    if (plan->mode == RAR_MODE_STEPWISE) return rar::launch_stepwise(*plan, ptrs, st);
+    Tuning t;
+    rc = fused_tuning(plan, &t);
+    if (rc != RAR_OK) return rc;
+    rc = ensure_flags(plan, st);
+    if (rc != RAR_OK) return rc;
+    return rar::launch_fused(*plan, ptrs, t, true, st);
+}
+
+int rar_launch_floor(rar_plan_t *plan, void *stream) {
+    if (!plan) return RAR_ERR_ARG;
+    Tuning t;
+    int rc = fused_tuning(plan, &t);
+    if (rc != RAR_OK) return rc;
+    return rar::launch_empty(static_cast<unsigned>(plan->geo.P) * t.B_s, as_stream(stream));
+}
+
+int rar_barrier_only(rar_plan_t *plan, void *stream) {
+    if (!plan) return RAR_ERR_ARG;
+    int rc = ensure_scratch(plan);
+    if (rc != RAR_OK) return rc;
+    Tuning t;
+    rc = fused_tuning(plan, &t);
+    if (rc != RAR_OK) return rc;
+    hipStream_t st = as_stream(stream);
+    rc = ensure_flags(plan, st);
+    if (rc != RAR_OK) return rc;
+    RankPtrs ptrs;
+    std::memset(&ptrs, 0, sizeof ptrs);
+    return rar::launch_fused(*plan, ptrs, t, false, st);
+}
+
+int rar_copy_probe(void *dst, const void *src, size_t bytes, void *stream) {
+    if (!dst || !src) return RAR_ERR_ARG;
+    if ((reinterpret_cast<uintptr_t>(dst) | reinterpret_cast<uintptr_t>(src) | bytes) % 16 != 0) return RAR_ERR_ALIGN;
+    return rar::launch_copy(dst, src, bytes / 16, as_stream(stream));
+}
+
+}  // extern "C"

@@ -1,0 +1,611 @@
+// gfx950 kernels of the hierarchical recursive-doubling all-reduce (Algorithm 1 and Section
+// 4.1 of the paper) and their launchers.  HBM-bound streaming work: 16-byte vector loads and
+// stores, binary32 accumulation, no matrix cores.
+//
+// Vocabulary: a rank's message is cut into G chunks; chunk c belongs to local rank c.  A
+// chunk is cut into slices of kThreads*U 16-byte vectors; a workgroup moves one slice per
+// trip (the paper's C_s), and B_s workgroups serve a rank (Section 4.2.1).  S_l(p) is rank
+// p's partial after l inter-node steps, one scratch buffer per step so that a rank may run
+// ahead of its peer (Section 4.2.1, per-step send/receive buffers).
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "launch.hpp"
+
+namespace rar {
+
+typedef uint32_t u32;
+typedef uint64_t u64;
+
+// ---- element arithmetic -----------------------------------------------------------------------
+
+__device__ __forceinline__ float bits_f(u32 u) { return __uint_as_float(u); }
+__device__ __forceinline__ u32 f_bits(float f) { return __float_as_uint(f); }
+
+// binary32 -> bf16 bits, round to nearest, ties to even; NaN stays NaN (quiet).
+__device__ __forceinline__ u32 narrow_bf16(float f) {
+    const u32 u = f_bits(f);
+    const u32 r = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+    return (u & 0x7fffffffu) > 0x7f800000u ? ((u >> 16) | 0x40u) : r;
+}
+
+// A 16-byte vector as binary32 lanes: 8 for bf16, 4 for fp32.
+template <int DT> struct Lanes;
+template <> struct Lanes<RAR_BF16> {
+    static constexpr int kCount = 8;
+    float f[8];
+    __device__ __forceinline__ void widen(const uint4 &v) {
+        f[0] = bits_f(v.x << 16); f[1] = bits_f(v.x & 0xffff0000u);
+        f[2] = bits_f(v.y << 16); f[3] = bits_f(v.y & 0xffff0000u);
+        f[4] = bits_f(v.z << 16); f[5] = bits_f(v.z & 0xffff0000u);
+        f[6] = bits_f(v.w << 16); f[7] = bits_f(v.w & 0xffff0000u);
+    }
+    __device__ __forceinline__ uint4 narrow() const {
+        uint4 v;
+        v.x = narrow_bf16(f[0]) | (narrow_bf16(f[1]) << 16);
+        v.y = narrow_bf16(f[2]) | (narrow_bf16(f[3]) << 16);
+        v.z = narrow_bf16(f[4]) | (narrow_bf16(f[5]) << 16);
+        v.w = narrow_bf16(f[6]) | (narrow_bf16(f[7]) << 16);
+        return v;
+    }
+};
+template <> struct Lanes<RAR_F32> {
+    static constexpr int kCount = 4;
+    float f[4];
+    __device__ __forceinline__ void widen(const uint4 &v) {
+        f[0] = bits_f(v.x); f[1] = bits_f(v.y); f[2] = bits_f(v.z); f[3] = bits_f(v.w);
+    }
+    __device__ __forceinline__ uint4 narrow() const {
+        return make_uint4(f_bits(f[0]), f_bits(f[1]), f_bits(f[2]), f_bits(f[3]));
+    }
+};
+
+template <int DT>
+__device__ __forceinline__ void add_into(Lanes<DT> &acc, const uint4 &v) {
+    Lanes<DT> t;
+    t.widen(v);
+#pragma unroll
+    for (int i = 0; i < Lanes<DT>::kCount; ++i) acc.f[i] = acc.f[i] + t.f[i];
+}
+
+// narrow( widen(a) + widen(b) ): one exchange-and-sum on a vector.
+template <int DT>
+__device__ __forceinline__ uint4 combine(const uint4 &a, const uint4 &b) {
+    Lanes<DT> acc;
+    acc.widen(a);
+    add_into<DT>(acc, b);
+    return acc.narrow();
+}
+
+__device__ __forceinline__ uint4 ld16(const void *base, u64 vec) {
+    return reinterpret_cast<const uint4 *>(base)[vec];
+}
+__device__ __forceinline__ void st16(void *base, u64 vec, const uint4 &v) {
+    reinterpret_cast<uint4 *>(base)[vec] = v;
+}
+
+// The one vector of a message that is only partly inside it (n not a multiple of the vector
+// width): element-wise access, padding with zeros.
+template <int DT>
+__device__ __forceinline__ uint4 ld_partial(const void *base, u64 vec, u32 count) {
+    u32 w[4] = {0u, 0u, 0u, 0u};
+    if (DT == RAR_BF16) {
+        const uint16_t *e = reinterpret_cast<const uint16_t *>(base) + vec * 8;
+        for (u32 i = 0; i < count; ++i) w[i >> 1] |= static_cast<u32>(e[i]) << ((i & 1u) * 16);
+    } else {
+        const u32 *e = reinterpret_cast<const u32 *>(base) + vec * 4;
+        for (u32 i = 0; i < count; ++i) w[i] = e[i];
+    }
+    return make_uint4(w[0], w[1], w[2], w[3]);
+}
+template <int DT>
+__device__ __forceinline__ void st_partial(void *base, u64 vec, u32 count, const uint4 &v) {
+    const u32 w[4] = {v.x, v.y, v.z, v.w};
+    if (DT == RAR_BF16) {
+        uint16_t *e = reinterpret_cast<uint16_t *>(base) + vec * 8;
+        for (u32 i = 0; i < count; ++i) e[i] = static_cast<uint16_t>(w[i >> 1] >> ((i & 1u) * 16));
+    } else {
+        u32 *e = reinterpret_cast<u32 *>(base) + vec * 4;
+        for (u32 i = 0; i < count; ++i) e[i] = w[i];
+    }
+}
+
+// Message vector `m` of a rank's buffer: whole, partial (the last one) or outside.
+template <int DT>
+__device__ __forceinline__ uint4 ld_message(const void *base, u32 m, u32 full_vecs, u32 tail) {
+    if (m < full_vecs) return ld16(base, m);
+    if (m == full_vecs && tail) return ld_partial<DT>(base, m, tail);
+    return make_uint4(0u, 0u, 0u, 0u);
+}
+template <int DT>
+__device__ __forceinline__ void st_message(void *base, u32 m, u32 full_vecs, u32 tail, const uint4 &v) {
+    if (m < full_vecs) st16(base, m, v);
+    else if (m == full_vecs && tail) st_partial<DT>(base, m, tail, v);
+}
+
+// ---- the three phases on one slice ---------------------------------------------------------
+
+struct Shape {
+    unsigned char *scratch;  // device
+    u64 chunk_stride;        // bytes between S buffers
+    u64 flags_offset;
+    u64 data_offset;
+    u64 wait_ticks;          // step-barrier time limit in 100 MHz ticks
+    u32 P, G, N, L;
+    u32 chunk_vecs;          // vectors per full chunk
+    u32 full_vecs;           // whole vectors in a message
+    u32 tail;                // elements in the partial last vector (0 = none)
+    u32 B_s;                 // workgroups per rank
+    u32 iters;               // trips per workgroup
+    u32 xcd_map;             // 1: place all nodes' workgroups of one (chunk, slot) on one XCD
+};
+
+__device__ __forceinline__ unsigned char *partial_buf(const Shape &s, u32 level, u32 rank) {
+    return s.scratch + s.data_offset + (static_cast<u64>(level) * s.P + rank) * s.chunk_stride;
+}
+
+// Vectors of chunk c that lie inside the message (the last chunks may be short or empty).
+__device__ __forceinline__ u32 chunk_valid_vecs(const Shape &s, u32 c) {
+    const u32 total = s.full_vecs + (s.tail ? 1u : 0u);
+    const u64 begin = static_cast<u64>(c) * s.chunk_vecs;
+    if (begin >= total) return 0u;
+    const u64 left = total - begin;
+    return left < s.chunk_vecs ? static_cast<u32>(left) : s.chunk_vecs;
+}
+
+// Phase 1 on one slice: part[u] = narrow( x(r_n,0) + x(r_n,1) + .. + x(r_n,G-1) ), binary32,
+// local rank order (Section 4.1, reduce-scatter).  GT = compile-time G, 0 = run-time G.
+template <int DT, int GT, int U>
+__device__ __forceinline__ void reduce_scatter_slice(const RankPtrs &bufs, const Shape &s, u32 r_n,
+                                                     u32 c, u32 v0, u32 valid, bool whole,
+                                                     uint4 (&part)[U]) {
+    const u32 G = GT ? GT : s.G;
+    const u32 mbase = c * s.chunk_vecs;
+    Lanes<DT> acc[U];
+    if (whole) {
+        // every vector of the slice is a whole vector inside the message: no checks
+        constexpr int GB = GT == 0 ? 1 : (GT * U <= 32 ? GT : (32 / U > 0 ? 32 / U : 1));
+        uint4 in[GB][U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) acc[u].widen(ld16(bufs.p[r_n * G], mbase + v0 + u * kThreads));
+        for (u32 g0 = 1; g0 < G; g0 += GB) {
+#pragma unroll
+            for (int gb = 0; gb < GB; ++gb) {
+                if (g0 + gb < G) {
+                    const void *x = bufs.p[r_n * G + g0 + gb];
+#pragma unroll
+                    for (int u = 0; u < U; ++u) in[gb][u] = ld16(x, mbase + v0 + u * kThreads);
+                }
+            }
+#pragma unroll
+            for (int gb = 0; gb < GB; ++gb) {
+                if (g0 + gb < G) {
+#pragma unroll
+                    for (int u = 0; u < U; ++u) add_into<DT>(acc[u], in[gb][u]);
+                }
+            }
+        }
+    } else {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const u32 v = v0 + u * kThreads;
+            if (v < valid) {
+                acc[u].widen(ld_message<DT>(bufs.p[r_n * G], mbase + v, s.full_vecs, s.tail));
+                for (u32 g = 1; g < G; ++g)
+                    add_into<DT>(acc[u], ld_message<DT>(bufs.p[r_n * G + g], mbase + v, s.full_vecs, s.tail));
+            } else {
+                acc[u].widen(make_uint4(0u, 0u, 0u, 0u));
+            }
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) part[u] = acc[u].narrow();
+}
+
+// Phase 3 on one slice: put the reduced slice into chunk c of all G buffers of the node
+// (Section 4.1, all-gather).
+template <int DT, int GT, int U>
+__device__ __forceinline__ void all_gather_slice(const RankPtrs &bufs, const Shape &s, u32 r_n, u32 c,
+                                                 u32 v0, u32 valid, bool whole, const uint4 (&part)[U]) {
+    const u32 G = GT ? GT : s.G;
+    const u32 mbase = c * s.chunk_vecs;
+    for (u32 g = 0; g < G; ++g) {
+        void *x = bufs.p[r_n * G + g];
+        if (whole) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) st16(x, mbase + v0 + u * kThreads, part[u]);
+        } else {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const u32 v = v0 + u * kThreads;
+                if (v < valid) st_message<DT>(x, mbase + v, s.full_vecs, s.tail, part[u]);
+            }
+        }
+    }
+}
+
+template <int U>
+__device__ __forceinline__ void store_slice(unsigned char *S, u32 v0, u32 valid, bool whole,
+                                            const uint4 (&part)[U]) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const u32 v = v0 + u * kThreads;
+        if (whole || v < valid) st16(S, v, part[u]);
+    }
+}
+
+template <int U>
+__device__ __forceinline__ void load_slice(const unsigned char *S, u32 v0, u32 valid, bool whole,
+                                           uint4 (&out)[U]) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const u32 v = v0 + u * kThreads;
+        out[u] = (whole || v < valid) ? ld16(S, v) : make_uint4(0u, 0u, 0u, 0u);
+    }
+}
+
+// ---- step barrier (Algorithm 1: "wait until flag(dst_q) == seq") ---------------------------
+//
+// One 32-bit flag per (step buffer, rank, workgroup slot).  The value is a trip counter that
+// only ever grows (the paper's sequence number: flags are never cleared between calls), so a
+// consumer waits for "at least the value of my own trip", compared as a signed difference.
+
+__device__ __forceinline__ u32 *flag_ptr(const Shape &s, u32 level, u32 rank, u32 slot) {
+    u32 *flags = reinterpret_cast<u32 *>(s.scratch + s.flags_offset);
+    return flags + (static_cast<u64>(level) * s.P + rank) * kMaxWorkgroupsPerRank + slot;
+}
+
+// All of the workgroup's stores to S are made visible device-wide, then the flag is raised.
+__device__ __forceinline__ void publish(u32 *flag, u32 value) {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_waitcnt(0);  // this wave's stores have been accepted by its L2
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");  // write the L2's dirty lines back
+        __builtin_amdgcn_s_waitcnt(0);                      // ... and wait until that is done
+        __hip_atomic_store(flag, value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+// Thread 0 polls; the wait is bounded by wall-clock time and by the shared status word, so
+// every workgroup leaves the kernel even if a peer never arrives.
+__device__ __forceinline__ void wait_for(const Shape &s, const u32 *flag, u32 expect, bool &gave_up) {
+    if (threadIdx.x == 0) {
+        if (!gave_up) {
+            u32 *status = reinterpret_cast<u32 *>(s.scratch);
+            const u64 t0 = wall_clock64();
+            u32 spins = 0;
+            for (;;) {
+                const u32 seen = __hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (static_cast<int>(seen - expect) >= 0) break;
+                __builtin_amdgcn_s_sleep(1);
+                if ((++spins & 31u) == 0u) {
+                    const bool late = wall_clock64() - t0 > s.wait_ticks;
+                    if (late) __hip_atomic_store(status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if (late || __hip_atomic_load(status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) {
+                        gave_up = true;
+                        break;
+                    }
+                }
+            }
+        }
+    }
+    __syncthreads();
+    // every wave drops stale L1/L2 lines itself, in program order before its own loads
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+}
+
+// Workgroup index -> (node, chunk, slot).  Workgroups are dealt to the 8 XCDs round-robin by
+// index, and each XCD has its own L2.  Slices are exchanged only among the N workgroups
+// (one per node) that share (chunk, slot), so those N are given indices on one XCD when the
+// number of (chunk, slot) pairs is a multiple of 8.  Correctness never depends on placement.
+__device__ __forceinline__ void locate(const Shape &s, u32 block, u32 &r_n, u32 &c, u32 &slot) {
+    u32 pair;
+    if (s.xcd_map) {
+        const u32 xcd = block & 7u, idx = block >> 3;
+        pair = (idx / s.N) * 8u + xcd;
+        r_n = idx % s.N;
+    } else {
+        pair = block / s.N;
+        r_n = block % s.N;
+    }
+    c = pair % s.G;
+    slot = pair / s.G;
+}
+
+// ---- the fused schedule: phases 1-3 of Algorithm 1 in one persistent launch -----------------
+//
+// Workgroup (rank p = (r_n, c), slot w) owns slices w, w + B_s, .. of chunk c.  Per slice:
+// reduce-scatter into registers, publish S_0, then for each step wait for the peer's S_l,
+// add it to the partial held in registers, publish S_{l+1} (the last step's result is not
+// exchanged, so it is not written to scratch), finally all-gather from registers.
+// DATA = false leaves all data movement out (barrier traffic only, for measurement).
+template <int DT, int GT, int U, bool DATA>
+__global__ __launch_bounds__(kThreads) void fused_kernel(RankPtrs bufs, Shape s) {
+    u32 r_n, c, w;
+    locate(s, blockIdx.x, r_n, c, w);
+    const u32 G = GT ? GT : s.G;
+    const u32 p = r_n * G + c;
+    const u32 valid_vecs = chunk_valid_vecs(s, c);
+    // vectors of this chunk that are whole vectors of the message
+    const u64 cbegin = static_cast<u64>(c) * s.chunk_vecs;
+    const u32 whole_vecs = s.full_vecs > cbegin
+                               ? (s.full_vecs - cbegin < valid_vecs ? static_cast<u32>(s.full_vecs - cbegin) : valid_vecs)
+                               : 0u;
+    // this slot's counter as the previous call left it (all ranks' slot w hold the same value)
+    const u32 base = s.L ? __hip_atomic_load(flag_ptr(s, 0, p, w), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
+    bool gave_up = false;
+
+    for (u32 it = 0; it < s.iters; ++it) {
+        const u32 slice = w + it * s.B_s;
+        const u64 first = static_cast<u64>(slice) * (kThreads * U);
+        const u32 v0 = static_cast<u32>(first) + threadIdx.x;  // first < 2^31 by construction
+        const bool whole = first + kThreads * U <= whole_vecs;
+        const u32 valid = first < valid_vecs ? valid_vecs : 0u;  // slices past the chunk do nothing
+        const u32 ticket = base + it + 1u;
+
+        uint4 part[U];
+        if (DATA) reduce_scatter_slice<DT, GT, U>(bufs, s, r_n, c, v0, valid, whole, part);
+        if (s.L) {
+            if (DATA) store_slice<U>(partial_buf(s, 0, p), v0, valid, whole, part);
+            publish(flag_ptr(s, 0, p, w), ticket);
+        }
+        for (u32 l = 0; l < s.L; ++l) {
+            const u32 peer = (r_n ^ (1u << l)) * G + c;
+            wait_for(s, flag_ptr(s, l, peer, w), ticket, gave_up);
+            if (DATA) {
+                uint4 got[U];
+                load_slice<U>(partial_buf(s, l, peer), v0, valid, whole, got);
+#pragma unroll
+                for (int u = 0; u < U; ++u) part[u] = combine<DT>(got[u], part[u]);
+            }
+            if (l + 1 < s.L) {
+                if (DATA) store_slice<U>(partial_buf(s, l + 1, p), v0, valid, whole, part);
+                publish(flag_ptr(s, l + 1, p, w), ticket);
+            }
+        }
+        if (DATA) all_gather_slice<DT, GT, U>(bufs, s, r_n, c, v0, valid, whole, part);
+    }
+}
+
+// ---- stepwise kernels: one launch per phase, one slice per workgroup -------------------------
+
+struct StepShape {
+    Shape s;
+    u32 slices;  // slices per rank; grid = P * slices
+};
+
+template <int DT, int U>
+__device__ __forceinline__ void step_locate(const StepShape &a, u32 &p, u32 &r_n, u32 &c, u32 &v0,
+                                            u32 &valid, bool &whole) {
+    p = blockIdx.x / a.slices;
+    const u32 slice = blockIdx.x % a.slices;
+    r_n = p / a.s.G;
+    c = p % a.s.G;
+    const u32 valid_vecs = chunk_valid_vecs(a.s, c);
+    const u64 cbegin = static_cast<u64>(c) * a.s.chunk_vecs;
+    const u32 whole_vecs = a.s.full_vecs > cbegin
+                               ? (a.s.full_vecs - cbegin < valid_vecs ? static_cast<u32>(a.s.full_vecs - cbegin) : valid_vecs)
+                               : 0u;
+    const u64 first = static_cast<u64>(slice) * (kThreads * U);
+    v0 = static_cast<u32>(first) + threadIdx.x;
+    whole = first + kThreads * U <= whole_vecs;
+    valid = first < valid_vecs ? valid_vecs : 0u;
+}
+
+template <int DT, int U>
+__global__ __launch_bounds__(kThreads) void reduce_scatter_kernel(RankPtrs bufs, StepShape a) {
+    u32 p, r_n, c, v0, valid;
+    bool whole;
+    step_locate<DT, U>(a, p, r_n, c, v0, valid, whole);
+    uint4 part[U];
+    reduce_scatter_slice<DT, 0, U>(bufs, a.s, r_n, c, v0, valid, whole, part);
+    store_slice<U>(partial_buf(a.s, 0, p), v0, valid, whole, part);
+}
+
+// S_{l+1}(p) = narrow( S_l(peer) + S_l(p) )  (Algorithm 1, RD_inter, one step for all ranks)
+template <int DT, int U>
+__global__ __launch_bounds__(kThreads) void exchange_sum_kernel(StepShape a, u32 l) {
+    u32 p, r_n, c, v0, valid;
+    bool whole;
+    step_locate<DT, U>(a, p, r_n, c, v0, valid, whole);
+    const u32 peer = (r_n ^ (1u << l)) * a.s.G + c;
+    uint4 own[U], got[U];
+    load_slice<U>(partial_buf(a.s, l, p), v0, valid, whole, own);
+    load_slice<U>(partial_buf(a.s, l, peer), v0, valid, whole, got);
+#pragma unroll
+    for (int u = 0; u < U; ++u) own[u] = combine<DT>(got[u], own[u]);
+    store_slice<U>(partial_buf(a.s, l + 1, p), v0, valid, whole, own);
+}
+
+template <int DT, int U>
+__global__ __launch_bounds__(kThreads) void all_gather_kernel(RankPtrs bufs, StepShape a) {
+    u32 p, r_n, c, v0, valid;
+    bool whole;
+    step_locate<DT, U>(a, p, r_n, c, v0, valid, whole);
+    uint4 part[U];
+    load_slice<U>(partial_buf(a.s, a.s.L, p), v0, valid, whole, part);
+    all_gather_slice<DT, 0, U>(bufs, a.s, r_n, c, v0, valid, whole, part);
+}
+
+// ---- single-rank exchange-and-sum, in place on dst ------------------------------------------
+
+template <int DT>
+__global__ __launch_bounds__(kThreads) void combine_kernel(unsigned char *dst, const unsigned char *src,
+                                                           u64 full_vecs, u32 tail) {
+    const u64 stride = static_cast<u64>(gridDim.x) * kThreads;
+    for (u64 v = static_cast<u64>(blockIdx.x) * kThreads + threadIdx.x; v < full_vecs; v += stride)
+        st16(dst, v, combine<DT>(ld16(dst, v), ld16(src, v)));
+    if (tail && blockIdx.x == 0 && threadIdx.x == 0) {
+        const uint4 r = combine<DT>(ld_partial<DT>(dst, full_vecs, tail), ld_partial<DT>(src, full_vecs, tail));
+        st_partial<DT>(dst, full_vecs, tail, r);
+    }
+}
+
+// ---- small utilities ---------------------------------------------------------------------------
+
+__global__ __launch_bounds__(kThreads) void fill_zero_kernel(u32 *words, u64 count) {
+    const u64 stride = static_cast<u64>(gridDim.x) * kThreads;
+    for (u64 i = static_cast<u64>(blockIdx.x) * kThreads + threadIdx.x; i < count; i += stride) words[i] = 0u;
+}
+
+__global__ __launch_bounds__(kThreads) void empty_kernel() {}
+
+__global__ __launch_bounds__(kThreads) void copy_kernel(uint4 *dst, const uint4 *src, u64 vecs) {
+    const u64 stride = static_cast<u64>(gridDim.x) * kThreads;
+    for (u64 v = static_cast<u64>(blockIdx.x) * kThreads + threadIdx.x; v < vecs; v += stride) dst[v] = src[v];
+}
+
+// ---- launchers ---------------------------------------------------------------------------------
+
+static Shape make_shape(const rar_plan_t &plan, const Tuning &t, bool xcd_map) {
+    const Geometry &g = plan.geo;
+    Shape s{};
+    s.scratch = static_cast<unsigned char *>(plan.scratch);
+    s.chunk_stride = g.chunk_stride;
+    s.flags_offset = g.flags_offset;
+    s.data_offset = g.data_offset;
+    s.wait_ticks = plan.wait_limit_us * 100ull;  // the wall clock counts at 100 MHz
+    s.P = g.P; s.G = g.G; s.N = g.N; s.L = g.L;
+    s.chunk_vecs = static_cast<u32>(g.chunk_vecs);
+    s.full_vecs = static_cast<u32>(g.n / g.per_vec);
+    s.tail = static_cast<u32>(g.n % g.per_vec);
+    s.B_s = t.B_s;
+    s.iters = t.iters;
+    s.xcd_map = xcd_map ? 1u : 0u;
+    return s;
+}
+
+typedef void (*FusedFn)(RankPtrs, Shape);
+
+template <int DT, int GT, bool DATA>
+static FusedFn pick_unroll(int unroll) {
+    switch (unroll) {
+        case 1: return fused_kernel<DT, GT, 1, DATA>;
+        case 2: return fused_kernel<DT, GT, 2, DATA>;
+        case 4: return fused_kernel<DT, GT, 4, DATA>;
+        default: return fused_kernel<DT, GT, 8, DATA>;
+    }
+}
+template <int DT, bool DATA>
+static FusedFn pick_group(int G, int unroll) {
+    switch (G) {
+        case 1: return pick_unroll<DT, 1, DATA>(unroll);
+        case 2: return pick_unroll<DT, 2, DATA>(unroll);
+        case 4: return pick_unroll<DT, 4, DATA>(unroll);
+        case 8: return pick_unroll<DT, 8, DATA>(unroll);
+        default: return pick_unroll<DT, 0, DATA>(unroll);
+    }
+}
+static FusedFn pick_fused(int dtype, int G, int unroll, bool data) {
+    if (dtype == RAR_BF16) return data ? pick_group<RAR_BF16, true>(G, unroll) : pick_group<RAR_BF16, false>(G, unroll);
+    return data ? pick_group<RAR_F32, true>(G, unroll) : pick_group<RAR_F32, false>(G, unroll);
+}
+
+int device_info(DeviceInfo *out) {
+    static DeviceInfo cached[16];
+    static bool have[16] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return RAR_ERR_HIP;
+    if (dev < 0 || dev >= 16) return RAR_ERR_HIP;
+    if (!have[dev]) {
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+            return RAR_ERR_HIP;
+        cached[dev].compute_units = cus;
+        have[dev] = true;
+    }
+    *out = cached[dev];
+    return RAR_OK;
+}
+
+int fused_max_resident(int dtype, int G, int unroll, long *out) {
+    DeviceInfo info;
+    int rc = device_info(&info);
+    if (rc != RAR_OK) return rc;
+    int per_cu = 0;
+    FusedFn fn = pick_fused(dtype, G, unroll, true);
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(fn), kThreads, 0) !=
+            hipSuccess || per_cu < 1)
+        return RAR_ERR_HIP;
+    *out = static_cast<long>(per_cu) * info.compute_units;
+    return RAR_OK;
+}
+
+static int check_launch() { return hipGetLastError() == hipSuccess ? RAR_OK : RAR_ERR_HIP; }
+
+int launch_fill_zero(void *words, size_t bytes, hipStream_t stream) {
+    const u64 count = bytes / 4;
+    u64 blocks = (count + kThreads - 1) / kThreads;
+    if (blocks > 1024) blocks = 1024;
+    if (blocks == 0) return RAR_OK;
+    fill_zero_kernel<<<dim3(static_cast<u32>(blocks)), dim3(kThreads), 0, stream>>>(static_cast<u32 *>(words), count);
+    return check_launch();
+}
+
+int launch_fused(const rar_plan_t &plan, const RankPtrs &bufs, const Tuning &t, bool data, hipStream_t stream) {
+    const Geometry &g = plan.geo;
+    const u32 pairs = static_cast<u32>(g.G) * t.B_s;
+    const Shape s = make_shape(plan, t, pairs % 8 == 0);
+    const u32 grid = static_cast<u32>(g.P) * t.B_s;
+    FusedFn fn = pick_fused(g.dtype, g.G, t.unroll, data);
+    fn<<<dim3(grid), dim3(kThreads), 0, stream>>>(bufs, s);
+    return check_launch();
+}
+
+int launch_empty(unsigned grid, hipStream_t stream) {
+    empty_kernel<<<dim3(grid), dim3(kThreads), 0, stream>>>();
+    return check_launch();
+}
+
+template <int DT>
+static int launch_stepwise_t(const rar_plan_t &plan, const RankPtrs &bufs, hipStream_t stream) {
+    constexpr int U = 4;
+    const Geometry &g = plan.geo;
+    Tuning t{1, U, 1};
+    StepShape a{};
+    a.s = make_shape(plan, t, false);
+    a.slices = static_cast<u32>((g.chunk_vecs + kThreads * U - 1) / (kThreads * U));
+    const u64 grid64 = static_cast<u64>(g.P) * a.slices;
+    if (grid64 >= (1ull << 31)) return RAR_ERR_LIMIT;
+    const dim3 grid(static_cast<u32>(grid64)), block(kThreads);
+    reduce_scatter_kernel<DT, U><<<grid, block, 0, stream>>>(bufs, a);
+    if (check_launch() != RAR_OK) return RAR_ERR_HIP;
+    for (int l = 0; l < g.L; ++l) {
+        exchange_sum_kernel<DT, U><<<grid, block, 0, stream>>>(a, static_cast<u32>(l));
+        if (check_launch() != RAR_OK) return RAR_ERR_HIP;
+    }
+    all_gather_kernel<DT, U><<<grid, block, 0, stream>>>(bufs, a);
+    return check_launch();
+}
+
+int launch_stepwise(const rar_plan_t &plan, const RankPtrs &bufs, hipStream_t stream) {
+    return plan.geo.dtype == RAR_BF16 ? launch_stepwise_t<RAR_BF16>(plan, bufs, stream)
+                                      : launch_stepwise_t<RAR_F32>(plan, bufs, stream);
+}
+
+int launch_combine(void *dst, const void *src, size_t full_vecs, unsigned tail, int dtype, hipStream_t stream) {
+    u64 blocks = (full_vecs + kThreads - 1) / kThreads;
+    if (blocks == 0) blocks = 1;
+    if (blocks > 16384) blocks = 16384;
+    const dim3 grid(static_cast<u32>(blocks)), block(kThreads);
+    if (dtype == RAR_BF16)
+        combine_kernel<RAR_BF16><<<grid, block, 0, stream>>>(static_cast<unsigned char *>(dst),
+                                                             static_cast<const unsigned char *>(src), full_vecs, tail);
+    else
+        combine_kernel<RAR_F32><<<grid, block, 0, stream>>>(static_cast<unsigned char *>(dst),
+                                                            static_cast<const unsigned char *>(src), full_vecs, tail);
+    return check_launch();
+}
+
+int launch_copy(void *dst, const void *src, size_t vecs, hipStream_t stream) {
+    u64 blocks = (vecs + kThreads - 1) / kThreads;
+    if (blocks == 0) return RAR_OK;
+    if (blocks > 16384) blocks = 16384;
+    copy_kernel<<<dim3(static_cast<u32>(blocks)), dim3(kThreads), 0, stream>>>(
+        static_cast<uint4 *>(dst), static_cast<const uint4 *>(src), vecs);
+    return check_launch();
+}
+
+}  // namespace rar

@@ -1,0 +1,206 @@
+// Planner and the host-only part of the C ABI (Algorithm 1's inputs and peer rule; the chunk
+// partition; scratch layout).  No HIP calls in this file.
+#include "plan.hpp"
+
+#include <new>
+
+namespace rar {
+
+static int log2_exact(int v) {
+    if (v < 1) return -1;
+    int l = 0;
+    while ((1 << l) < v) ++l;
+    return (1 << l) == v ? l : -1;
+}
+
+static int gcd(int a, int b) { return b == 0 ? a : gcd(b, a % b); }
+
+int make_geometry(int P, int G, size_t n, int dtype, Geometry *geo) {
+    if (!geo || P < 1 || G < 1 || n == 0) return RAR_ERR_ARG;
+    if (dtype != RAR_BF16 && dtype != RAR_F32) return RAR_ERR_DTYPE;
+    if (P > RAR_MAX_RANKS) return RAR_ERR_LIMIT;
+    if (P % G != 0) return RAR_ERR_SHAPE;
+    const int N = P / G;
+    const int L = log2_exact(N);
+    if (L < 0) return RAR_ERR_SHAPE;
+
+    Geometry g;
+    g.P = P; g.G = G; g.N = N; g.L = L; g.dtype = dtype; g.n = n;
+    g.elem_bytes = dtype == RAR_BF16 ? 2 : 4;
+    g.per_vec = 16 / g.elem_bytes;
+    const size_t per_rank = (n + static_cast<size_t>(G) - 1) / static_cast<size_t>(G);
+    g.chunk_len = round_up(per_rank, g.per_vec);
+    g.chunk_vecs = g.chunk_len / g.per_vec;
+    // Vector indices inside a chunk, and G*chunk_vecs over a message, are 32-bit in the kernels.
+    if (g.chunk_vecs * static_cast<size_t>(G) >= (static_cast<size_t>(1) << 31)) return RAR_ERR_LIMIT;
+    g.chunk_stride = round_up(g.chunk_vecs * 16, kAlign);
+    g.flags_offset = kHeaderBytes;
+    // One flag per (step buffer l < L, rank, workgroup slot); S_L is never exchanged.
+    g.flags_bytes = round_up(static_cast<size_t>(L > 0 ? L : 1) * P * kMaxWorkgroupsPerRank * 4, kAlign);
+    g.data_offset = g.flags_offset + g.flags_bytes;
+    g.scratch_bytes = g.data_offset + static_cast<size_t>(L + 1) * P * g.chunk_stride;
+    *geo = g;
+    return RAR_OK;
+}
+
+Tuning resolve_tuning(const rar_plan_t &plan, const long *max_resident) {
+    const Geometry &g = plan.geo;
+    // Keep G*B_s a multiple of the XCD count when possible, so that the workgroups of all
+    // nodes that exchange one slice can be placed on one XCD (see the launch mapping).
+    const int xcd_step = 8 / gcd(g.G, 8);
+    auto align_down = [&](long w) { return w >= xcd_step ? w / xcd_step * xcd_step : w; };
+    auto cap_for = [&](int unroll_index) {
+        long cap = kMaxWorkgroupsPerRank;
+        if (max_resident && max_resident[unroll_index] > 0) {
+            long fit = max_resident[unroll_index] / g.P;
+            if (fit < 1) fit = 1;
+            if (fit < cap) cap = fit;
+        }
+        return cap;
+    };
+    const size_t V = g.chunk_vecs;
+    auto slices = [&](int unroll) {
+        return static_cast<long>((V + static_cast<size_t>(kThreads) * unroll - 1) /
+                                 (static_cast<size_t>(kThreads) * unroll));
+    };
+
+    Tuning t{};
+    int index = 3;
+    if (plan.user_C_s) {
+        t.unroll = static_cast<int>(plan.user_C_s / (static_cast<size_t>(kThreads) * 16));
+        index = t.unroll == 1 ? 0 : t.unroll == 2 ? 1 : t.unroll == 4 ? 2 : 3;
+    } else {
+        // Smallest trip size that lets every slice have a workgroup of its own.
+        t.unroll = 8;
+        for (int i = 0; i < 4; ++i) {
+            if (slices(1 << i) <= align_down(cap_for(i))) { t.unroll = 1 << i; index = i; break; }
+        }
+    }
+    const long cap = cap_for(index);
+    const long all = slices(t.unroll);
+    long want;
+    if (plan.user_B_s) {
+        want = plan.user_B_s < cap ? plan.user_B_s : cap;
+        if (want > all) want = all;
+    } else {
+        want = all < cap ? all : cap;
+        const long down = align_down(want);
+        const long up = (want + xcd_step - 1) / xcd_step * xcd_step;
+        // one slice per workgroup if that fits; extra (idle) workgroups are cheaper than a trip
+        want = (up <= cap) ? up : down;
+    }
+    if (want < 1) want = 1;
+    t.B_s = static_cast<int>(want);
+    t.iters = static_cast<int>((all + want - 1) / want);
+    if (t.iters < 1) t.iters = 1;
+    return t;
+}
+
+}  // namespace rar
+
+using rar::Geometry;
+
+extern "C" {
+
+int rar_version(void) { return 100; }
+
+const char *rar_strerror(int status) {
+    switch (status) {
+        case RAR_OK: return "ok";
+        case RAR_ERR_ARG: return "invalid argument";
+        case RAR_ERR_SHAPE: return "G must divide P and N = P/G must be a power of two";
+        case RAR_ERR_DTYPE: return "unknown dtype";
+        case RAR_ERR_LIMIT: return "size beyond the library's limits";
+        case RAR_ERR_SCRATCH: return "scratch not set, too small or misaligned";
+        case RAR_ERR_ALIGN: return "data pointer not 16-byte aligned";
+        case RAR_ERR_HIP: return "HIP call failed";
+        case RAR_ERR_TIMEOUT: return "step barrier wait timed out";
+        case RAR_ERR_TUNING: return "unsupported B_s / C_s";
+        default: return "unknown status";
+    }
+}
+
+int rar_plan(int P, int G, size_t n, int dtype, rar_plan_t **out) {
+    if (!out) return RAR_ERR_ARG;
+    *out = nullptr;
+    Geometry geo;
+    int rc = rar::make_geometry(P, G, n, dtype, &geo);
+    if (rc != RAR_OK) return rc;
+    rar_plan_t *p = new (std::nothrow) rar_plan_t();
+    if (!p) return RAR_ERR_ARG;
+    p->geo = geo;
+    *out = p;
+    return RAR_OK;
+}
+
+int rar_plan_free(rar_plan_t *plan) {
+    delete plan;
+    return RAR_OK;
+}
+
+int rar_plan_ranks(const rar_plan_t *plan) { return plan ? plan->geo.P : RAR_ERR_ARG; }
+int rar_plan_nodes(const rar_plan_t *plan) { return plan ? plan->geo.N : RAR_ERR_ARG; }
+int rar_plan_steps(const rar_plan_t *plan) { return plan ? plan->geo.L : RAR_ERR_ARG; }
+
+int rar_plan_peer(const rar_plan_t *plan, int rank, int step) {
+    if (!plan) return RAR_ERR_ARG;
+    const Geometry &g = plan->geo;
+    if (rank < 0 || rank >= g.P || step < 0 || step >= g.L) return RAR_ERR_ARG;
+    const int r_n = rank / g.G, r_g = rank % g.G;
+    return (r_n ^ (1 << step)) * g.G + r_g;
+}
+
+int rar_plan_chunk(const rar_plan_t *plan, int c, size_t *offset, size_t *length) {
+    if (!plan || !offset || !length) return RAR_ERR_ARG;
+    const Geometry &g = plan->geo;
+    if (c < 0 || c >= g.G) return RAR_ERR_ARG;
+    *offset = rar::chunk_begin(g, c);
+    *length = rar::chunk_begin(g, c + 1) - *offset;
+    return RAR_OK;
+}
+
+size_t rar_plan_scratch_bytes(const rar_plan_t *plan) { return plan ? plan->geo.scratch_bytes : 0; }
+
+int rar_plan_set_scratch(rar_plan_t *plan, void *scratch, size_t bytes) {
+    if (!plan) return RAR_ERR_ARG;
+    if (!scratch || bytes < plan->geo.scratch_bytes ||
+        reinterpret_cast<uintptr_t>(scratch) % rar::kAlign != 0)
+        return RAR_ERR_SCRATCH;
+    plan->scratch = scratch;
+    plan->scratch_size = bytes;
+    plan->flags_clean = false;
+    return RAR_OK;
+}
+
+int rar_plan_set_mode(rar_plan_t *plan, int mode) {
+    if (!plan || (mode != RAR_MODE_STEPWISE && mode != RAR_MODE_FUSED)) return RAR_ERR_ARG;
+    plan->mode = mode;
+    return RAR_OK;
+}
+
+int rar_plan_get_mode(const rar_plan_t *plan) { return plan ? plan->mode : RAR_ERR_ARG; }
+
+int rar_plan_set_tuning(rar_plan_t *plan, int B_s, size_t C_s) {
+    if (!plan) return RAR_ERR_ARG;
+    if (B_s < 0 || B_s > rar::kMaxWorkgroupsPerRank) return RAR_ERR_TUNING;
+    if (C_s != 0 && C_s != 4096 && C_s != 8192 && C_s != 16384 && C_s != 32768) return RAR_ERR_TUNING;
+    plan->user_B_s = B_s;
+    plan->user_C_s = C_s;
+    return RAR_OK;
+}
+
+int rar_plan_get_tuning(const rar_plan_t *plan, int *B_s, size_t *C_s) {
+    if (!plan || !B_s || !C_s) return RAR_ERR_ARG;
+    rar::Tuning t = rar::resolve_tuning(*plan, plan->have_resident ? plan->resident : nullptr);
+    *B_s = t.B_s;
+    *C_s = static_cast<size_t>(rar::kThreads) * 16 * t.unroll;
+    return RAR_OK;
+}
+
+int rar_plan_set_wait_limit_us(rar_plan_t *plan, uint64_t microseconds) {
+    if (!plan || microseconds == 0) return RAR_ERR_ARG;
+    plan->wait_limit_us = microseconds;
+    return RAR_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,75 @@
+// Host-side schedule of the hierarchical recursive-doubling all-reduce (Algorithm 1 of the
+// paper): who is whose peer at which step, which elements form which chunk, where every
+// per-step partial buffer and barrier flag lives in the scratch.  Pure integer logic; no HIP.
+#pragma once
+
+#include <cstddef>
+#include <cstdint>
+
+#include "rar.h"
+
+namespace rar {
+
+constexpr int kThreads = 256;           // threads per workgroup of every kernel
+constexpr int kMaxWorkgroupsPerRank = 256;
+constexpr size_t kHeaderBytes = 256;    // scratch header: status word at offset 0
+constexpr size_t kAlign = 256;
+
+inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+struct Geometry {
+    int P = 0, G = 0, N = 0, L = 0;
+    int dtype = RAR_BF16;
+    size_t n = 0;            // elements per rank
+    size_t elem_bytes = 0;   // 2 or 4
+    size_t per_vec = 0;      // elements per 16-byte vector (8 or 4)
+    size_t chunk_len = 0;    // elements per full chunk (multiple of per_vec)
+    size_t chunk_vecs = 0;   // 16-byte vectors per full chunk
+    size_t chunk_stride = 0; // bytes between consecutive S buffers in the scratch
+    size_t flags_offset = 0; // byte offset of the barrier flags in the scratch
+    size_t flags_bytes = 0;
+    size_t data_offset = 0;  // byte offset of S_0(rank 0)
+    size_t scratch_bytes = 0;
+};
+
+}  // namespace rar
+
+struct rar_plan_s {
+    rar::Geometry geo;
+    int mode = RAR_MODE_FUSED;
+    int user_B_s = 0;          // 0 = built-in choice
+    size_t user_C_s = 0;       // 0 = built-in choice
+    uint64_t wait_limit_us = 5000000;
+    void *scratch = nullptr;   // device, borrowed
+    size_t scratch_size = 0;
+    bool flags_clean = false;  // header + flags zeroed since the last event that invalidated them
+    long resident[4] = {0, 0, 0, 0};  // cached residency of the fused kernel per unroll 1,2,4,8
+    bool have_resident = false;
+};
+
+namespace rar {
+
+// Fill geo from (P, G, n, dtype); returns a rar_status.
+int make_geometry(int P, int G, size_t n, int dtype, Geometry *geo);
+
+inline size_t chunk_begin(const Geometry &g, int c) {
+    size_t b = static_cast<size_t>(c) * g.chunk_len;
+    return b < g.n ? b : g.n;
+}
+
+// Byte offset of S_l(rank) in the scratch.
+inline size_t partial_offset(const Geometry &g, int level, int rank) {
+    return g.data_offset + (static_cast<size_t>(level) * g.P + rank) * g.chunk_stride;
+}
+
+struct Tuning {
+    int B_s;      // workgroups per rank
+    int unroll;   // 16-byte vectors per thread per trip (C_s = kThreads * 16 * unroll)
+    int iters;    // trips per workgroup: ceil(chunk_vecs / (B_s * kThreads * unroll))
+};
+
+// Resolve the plan's tuning.  max_resident[i] = workgroups the device can hold at once for
+// the fused kernel with unroll 1 << i (nullptr or 0 = no residency limit, for host-only use).
+Tuning resolve_tuning(const rar_plan_t &plan, const long *max_resident);
+
+}  // namespace rar

@@ -1,0 +1,299 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle, bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import rar_inputs as ri
+from gpu_util import assert_same_bits, to_device, to_host
+
+pytestmark = pytest.mark.gpu
+
+rar = pytest.importorskip("paper_2511_09557_amd") if torch.cuda.is_available() else None
+
+DT = {"bf16": 0, "f32": 1}
+NP = {"bf16": np.uint16, "f32": np.float32}
+MODES = {"stepwise": 0, "fused": 1}
+
+
+def run_gpu(x: np.ndarray, G: int, mode: str, B_s: int = 0, C_s: int = 0, calls: int = 1) -> np.ndarray:
+    P, n = x.shape
+    dtype = "bf16" if x.dtype == np.uint16 else "f32"
+    print(f"[gpu] allreduce P={P} G={G} n={n} {dtype} mode={mode} B_s={B_s} C_s={C_s} calls={calls}", flush=True)
+    ar = rar.AllReduce(P, G, n, DT[dtype], MODES[mode])
+    ar.set_tuning(B_s, C_s)
+    bufs = to_device(x)
+    for _ in range(calls):
+        ar(bufs)
+    assert ar.status() == 0
+    out = to_host(bufs, x.dtype)
+    ar.close()
+    return out
+
+
+# ---- one exchange-and-sum step ----------------------------------------------------------------
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("n,chunk", [(8, 0), (1000, 3), (4096, 1), (65536 + 8, 2), (1 << 20, 0), (5, 0), (1027, 0)])
+def test_step_combine(dtype, n, chunk):
+    print(f"[gpu] step_combine {dtype} n={n} chunk={chunk}", flush=True)
+    total = (chunk + 2) * n
+    x = ri.random_inputs(900 + n, 2, total, dtype)
+    dst, src = x[0].copy(), x[1].copy()
+    oracle.step_combine(dst, src, chunk, n)
+    d, s = to_device(x)
+    rar.rar_step_combine(d.data_ptr(), s.data_ptr(), chunk, n, DT[dtype], torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    assert_same_bits(to_host([d], x.dtype)[0], dst, "step_combine")
+    assert_same_bits(to_host([s], x.dtype)[0], x[1], "src untouched")
+
+
+def test_step_combine_rejects_bad_arguments():
+    a = torch.zeros(64, dtype=torch.bfloat16, device="cuda:0")
+    b = torch.zeros(64, dtype=torch.bfloat16, device="cuda:0")
+    with pytest.raises(rar.RarError):
+        rar.rar_step_combine(a.data_ptr() + 2, b.data_ptr(), 0, 8, 0)     # misaligned
+    with pytest.raises(rar.RarError):
+        rar.rar_step_combine(a.data_ptr(), b.data_ptr(), 1, 3, 0)         # offset 6 bytes
+    with pytest.raises(rar.RarError):
+        rar.rar_step_combine(a.data_ptr(), a.data_ptr(), 0, 8, 0)         # overlap
+    with pytest.raises(rar.RarError):
+        rar.rar_step_combine(a.data_ptr(), b.data_ptr(), 0, 8, 7)         # dtype
+    with pytest.raises(rar.RarError):
+        rar.rar_step_combine(0, b.data_ptr(), 0, 8, 0)                    # NULL
+    rar.rar_step_combine(a.data_ptr(), b.data_ptr(), 0, 0, 0)             # n = 0 is a no-op
+    torch.cuda.synchronize()
+
+
+# ---- the five workloads -------------------------------------------------------------------------
+
+@pytest.mark.parametrize("mode", ["stepwise", "fused"])
+@pytest.mark.parametrize("name", ["c1", "c1_int", "c2", "c3", "c4"])
+def test_workloads_bit_exact(name, mode):
+    w = ri.WORKLOADS[name]
+    x = ri.make_inputs(w)
+    want = oracle.allreduce(x, w.G, threads=8)
+    got = run_gpu(x, w.G, mode)
+    assert_same_bits(got, want, f"{name}/{mode}")
+    if name == "c1_int":
+        exact = ri.bf16_bits_to_f32(x).astype(np.int64).sum(axis=0).astype(np.float32)
+        assert np.array_equal(ri.bf16_bits_to_f32(got), np.broadcast_to(exact, got.shape))
+    # within the stated distance of the plain fp64 sum, away from cancellation
+    ref, mag = oracle.naive_sum_f64(x)
+    away = np.abs(ref) >= mag / 2
+    rel = np.abs(ri.bf16_bits_to_f32(got[0]).astype(np.float64)[away] - ref[away]) / np.abs(ref[away])
+    assert rel.max() <= 2.0 ** -7 * np.log2(w.P)
+
+
+SWEEP = [(8, 4), (16, 4), (32, 4), (64, 4), (128, 4), (64, 8)]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("P,G", SWEEP)
+def test_sweep_small_sizes_bit_exact(P, G, dtype):
+    for nbytes in (8 << 10, 64 << 10, 512 << 10):
+        w = ri.sweep_workload(P, G, nbytes, dtype)
+        x = ri.make_inputs(w)
+        want = oracle.allreduce(x, G, threads=8)
+        assert_same_bits(run_gpu(x, G, "fused"), want, w.name)
+        if nbytes == 64 << 10:
+            assert_same_bits(run_gpu(x, G, "stepwise"), want, w.name + "/stepwise")
+            ref, mag = oracle.naive_sum_f64(x)
+            if dtype == "f32":
+                sel = np.abs(ref) >= mag / 4
+                assert (np.abs(want[0].astype(np.float64)[sel] - ref[sel]) / np.abs(ref[sel])).max() <= 2.0 ** -20
+
+
+def test_sweep_large_size_sampled():
+    """64 MiB per rank at P = 8: the oracle checks a strided sample of columns (every element
+    is reduced independently, so the oracle on a column subset is the oracle's value there)."""
+    P, G, dtype = 8, 4, "bf16"
+    n = (64 << 20) // 2
+    rng = np.random.default_rng(ri.SEED_BASE + 499)
+    base = ri.to_bf16_bits(rng.standard_normal((P, 1 << 20), dtype=np.float32))
+    reps = n // base.shape[1]
+    bufs = []
+    for p in range(P):
+        row = torch.from_numpy(np.roll(base[p], 977 * p).view(np.int16).copy()).view(torch.bfloat16)
+        # tile the seeded block, each repeat scaled by an exact power of two so that columns differ
+        dev = row.to("cuda:0").repeat(reps).view(reps, -1)
+        scale = torch.tensor([2.0 ** ((r % 7) - 3) for r in range(reps)], dtype=torch.bfloat16, device="cuda:0")
+        bufs.append((dev * scale[:, None]).reshape(-1).contiguous())
+    cols = np.unique(np.concatenate([np.arange(0, n, 4099), np.arange(n - 4096, n), np.arange(0, 4096),
+                                     np.arange(n // 4 - 64, n // 4 + 64)]))
+    ci = torch.from_numpy(cols).to("cuda:0")
+    x_s = np.stack([b[ci].cpu().view(torch.int16).numpy().view(np.uint16) for b in bufs])
+    want = oracle.allreduce(x_s, G, threads=8)     # element-wise independent: chunking is irrelevant
+    for mode in ("fused", "stepwise"):
+        work = [b.clone() for b in bufs]
+        print(f"[gpu] large sampled P={P} n={n} mode={mode}", flush=True)
+        ar = rar.AllReduce(P, G, n, 0, MODES[mode])
+        ar(work)
+        assert ar.status() == 0
+        got = np.stack([b[ci].cpu().view(torch.int16).numpy().view(np.uint16) for b in work])
+        assert_same_bits(got, want, f"large/{mode}")
+        for p in range(1, P):
+            assert torch.equal(work[p].view(torch.int16), work[0].view(torch.int16))
+        ar.close()
+
+
+# ---- edge cases -------------------------------------------------------------------------------------
+
+EDGE = [(1, 1, 1), (1, 1, 1000), (2, 1, 9), (2, 2, 9), (4, 4, 3), (4, 2, 17), (8, 4, 1), (8, 4, 7),
+        (8, 4, 31), (8, 4, 33), (8, 4, 4 * 8 * 256 + 5), (8, 8, 1029), (16, 1, 4097), (16, 4, 65536 + 24),
+        (32, 8, 12345), (128, 4, 1001), (128, 8, 40000), (6, 3, 1000), (12, 3, 77), (5, 5, 64)]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("P,G,n", EDGE)
+def test_edge_shapes(P, G, n, dtype):
+    x = ri.random_inputs(5000 + P * 7 + n, P, n, dtype)
+    want = oracle.allreduce(x, G)
+    assert_same_bits(run_gpu(x, G, "fused"), want, "fused")
+    assert_same_bits(run_gpu(x, G, "stepwise"), want, "stepwise")
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_special_values(dtype):
+    P, G, n = 16, 4, 8192 + 3
+    rng = np.random.default_rng(42)
+    if dtype == "bf16":
+        pool = np.concatenate([ri.to_bf16_bits(np.array([0.0, -0.0, 2.0 ** -133, -2.0 ** -133, 2.0 ** -126, 3.0e38,
+                                                         -3.0e38, 1.0, 256.0, 257.0, 0.5], dtype=np.float32)),
+                               np.array([0x7F80, 0xFF80, 0x0001, 0x8001, 0x007F], dtype=np.uint16)])
+        x = pool[rng.integers(0, pool.size, size=(P, n))]
+        x[:, : n // 2] = rng.integers(0, 1 << 16, size=(P, n // 2), dtype=np.uint16)   # any bit pattern, NaN included
+    else:
+        pool = np.array([0.0, -0.0, 1e-45, -1e-45, 1e-40, 3e38, -3e38, np.inf, -np.inf, 2.0 ** 24, 1.0, 0.5, 1 / 3],
+                        dtype=np.float32)
+        x = pool[rng.integers(0, pool.size, size=(P, n))]
+        x[:, : n // 2] = rng.integers(0, 1 << 32, size=(P, n // 2), dtype=np.uint32).view(np.float32)
+    want = oracle.allreduce(x, G)
+    assert_same_bits(run_gpu(x, G, "fused"), want, "fused")
+    assert_same_bits(run_gpu(x, G, "stepwise"), want, "stepwise")
+
+
+@pytest.mark.parametrize("B_s,C_s", [(1, 4096), (2, 8192), (3, 4096), (8, 16384), (16, 32768), (256, 4096), (5, 0), (0, 8192)])
+def test_tuning_never_changes_bits(B_s, C_s):
+    w = ri.WORKLOADS["c2"]
+    x = ri.make_inputs(w)
+    want = oracle.allreduce(x, w.G, threads=8)
+    assert_same_bits(run_gpu(x, w.G, "fused", B_s=B_s, C_s=C_s), want, f"B_s={B_s} C_s={C_s}")
+
+
+def test_repeated_calls_in_place():
+    """Three chained in-place calls; flags are counters that are never cleared in between."""
+    w = ri.WORKLOADS["c1"]
+    x = ri.make_inputs(w)
+    x = ri.to_bf16_bits(ri.bf16_bits_to_f32(x) / 64.0)
+    want = x
+    for _ in range(3):
+        want = oracle.allreduce(want, w.G)
+    assert_same_bits(run_gpu(x, w.G, "fused", calls=3), want, "fused x3")
+    assert_same_bits(run_gpu(x, w.G, "fused", B_s=2, C_s=4096, calls=3), want, "fused x3, several trips")
+    assert_same_bits(run_gpu(x, w.G, "stepwise", calls=3), want, "stepwise x3")
+
+
+def test_fused_equals_stepwise_under_replay():
+    """Stress of the flag protocol: 200 fused calls with fresh inputs, each compared with the
+    stepwise path (which synchronises by kernel boundaries only)."""
+    P, G, n = 32, 4, 256 * 1024
+    a = rar.AllReduce(P, G, n, 0, 1)
+    b = rar.AllReduce(P, G, n, 0, 0)
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(1234)
+    print("[gpu] replay stress", flush=True)
+    for it in range(200):
+        src = torch.randn(P, n, device="cuda:0", generator=gen).to(torch.bfloat16)
+        xa = [src[p].clone() for p in range(P)]
+        xb = [src[p].clone() for p in range(P)]
+        if it % 3 == 1:
+            a.set_tuning(4, 8192)
+        elif it % 3 == 2:
+            a.set_tuning(0, 0)
+        a(xa)
+        b(xb)
+        for p in range(P):
+            assert torch.equal(xa[p].view(torch.int16), xb[0].view(torch.int16)), (it, p)
+    assert a.status() == 0
+    a.close(), b.close()
+
+
+def test_graph_replay():
+    """The fused call inside a HIP graph, replayed with eager work in between."""
+    w = ri.WORKLOADS["c2"]
+    x = ri.make_inputs(w)
+    want = oracle.allreduce(x, w.G, threads=8)
+    ar = rar.AllReduce(w.P, w.G, w.n, 0, 1)
+    src = to_device(x)
+    bufs = [t.clone() for t in src]
+    ar(bufs)                                   # eager warm-up: clears the flags once
+    torch.cuda.synchronize()
+    stream = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(stream):
+        for b, s in zip(bufs, src):
+            b.copy_(s)
+        with torch.cuda.graph(graph, stream=stream):
+            ar(bufs, stream)
+    for rep in range(4):
+        for b, s in zip(bufs, src):
+            b.copy_(s)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert_same_bits(to_host(bufs, x.dtype), want, f"graph replay {rep}")
+        ar(bufs)                               # eager call between replays advances the counters too
+        torch.cuda.synchronize()
+    assert ar.status() == 0
+    ar.close()
+
+
+def test_wait_limit_ends_every_workgroup():
+    """A 1-tick wait limit makes waits give up instead of spinning: the kernel must still
+    finish, report the time-out, and the plan must work again afterwards."""
+    w = ri.WORKLOADS["c3"]
+    x = ri.make_inputs(w)
+    want = oracle.allreduce(x, w.G, threads=8)
+    ar = rar.AllReduce(w.P, w.G, w.n, 0, 1)
+    ar.set_tuning(2, 4096)                     # many trips, so some wait is certain to be pending
+    bufs = to_device(x)
+    rar.rar_plan_set_wait_limit_us(ar.plan, 1)
+    print("[gpu] wait-limit run", flush=True)
+    timed_out = False
+    for _ in range(20):
+        ar(bufs)
+        if ar.status() == -8:
+            timed_out = True
+            break
+    rar.rar_plan_set_wait_limit_us(ar.plan, 5_000_000)
+    bufs = to_device(x)
+    ar(bufs)
+    assert ar.status() == 0
+    assert_same_bits(to_host(bufs, x.dtype), want, "after a time-out")
+    assert timed_out or True                   # a time-out is likely but not certain; recovery is what is checked
+
+
+def test_allreduce_rejects_bad_arguments():
+    P, G, n = 8, 4, 1024
+    plan = rar.rar_plan(P, G, n, 0)
+    bufs = [torch.zeros(n, dtype=torch.bfloat16, device="cuda:0") for _ in range(P)]
+    ptrs = [b.data_ptr() for b in bufs]
+    with pytest.raises(rar.RarError) as e:
+        rar.rar_allreduce(ptrs, plan)           # no scratch
+    assert e.value.status == -5
+    scratch = torch.empty(rar.rar_plan_scratch_bytes(plan) + 256, dtype=torch.uint8, device="cuda:0")
+    base = (scratch.data_ptr() + 255) // 256 * 256
+    with pytest.raises(rar.RarError):
+        rar.rar_plan_set_scratch(plan, base, 100)          # too small
+    with pytest.raises(rar.RarError):
+        rar.rar_plan_set_scratch(plan, base + 16, rar.rar_plan_scratch_bytes(plan))   # misaligned
+    rar.rar_plan_set_scratch(plan, base, rar.rar_plan_scratch_bytes(plan))
+    with pytest.raises(rar.RarError) as e:
+        rar.rar_allreduce([ptrs[0] + 2] + ptrs[1:], plan)
+    assert e.value.status == -6
+    with pytest.raises(rar.RarError):
+        rar.rar_allreduce([0] + ptrs[1:], plan)
+    rar.rar_allreduce(ptrs, plan)
+    torch.cuda.synchronize()
+    rar.rar_plan_free(plan)

@@ -1,0 +1,125 @@
+"""Host-only checks: the library loads, exports every symbol the header declares, and the
+planner's integer logic follows Algorithm 1 (peer rule, step count, chunk partition)."""
+import os
+import re
+
+import pytest
+
+import paper_2511_09557_amd as rar
+from paper_2511_09557_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_every_declared_symbol_is_exported():
+    header = open(os.path.join(ROOT, "include", "rar.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(rar_[a-z_0-9]+)\s*\(", header))
+    assert declared, "no declarations found"
+    for name in declared:
+        assert hasattr(binding.lib, name), f"{name} declared in rar.h but not exported"
+    assert declared == set(binding.EXPORTS)
+
+
+def test_version_and_strerror():
+    assert rar.rar_version() >= 100
+    for code in range(0, -10, -1):
+        assert rar.rar_strerror(code) != "unknown status"
+    assert rar.rar_strerror(-99) == "unknown status"
+
+
+@pytest.mark.parametrize("P,G,status", [(0, 1, -1), (8, 0, -1), (12, 4, -2), (10, 4, -2), (24, 8, -2),
+                                        (256, 4, -4), (8, 16, -2)])
+def test_plan_rejects(P, G, status):
+    with pytest.raises(rar.RarError) as e:
+        rar.rar_plan(P, G, 1024, 0)
+    assert e.value.status == status
+
+
+def test_plan_rejects_other():
+    with pytest.raises(rar.RarError) as e:
+        rar.rar_plan(8, 4, 0, 0)
+    assert e.value.status == -1
+    with pytest.raises(rar.RarError) as e:
+        rar.rar_plan(8, 4, 16, 5)
+    assert e.value.status == -3
+    with pytest.raises(rar.RarError) as e:
+        rar.rar_plan(8, 4, 1 << 40, 0)
+    assert e.value.status == -4
+
+
+def test_peer_rule_exhaustive():
+    for G in (1, 2, 3, 4, 8):
+        for N in (1, 2, 4, 8, 16, 32, 64, 128):
+            P = G * N
+            if P > 128:
+                continue
+            plan = rar.rar_plan(P, G, 4096, 0)
+            L = rar.rar_plan_steps(plan)
+            assert (1 << L) == N and rar.rar_plan_nodes(plan) == N and rar.rar_plan_ranks(plan) == P
+            for p in range(P):
+                r_n, r_g = divmod(p, G)
+                reached = {r_n}
+                for l in range(L):
+                    q = rar.rar_plan_peer(plan, p, l)
+                    assert q == (r_n ^ (1 << l)) * G + r_g
+                    assert q % G == r_g                       # same local id across nodes
+                    assert rar.rar_plan_peer(plan, q, l) == p  # the exchange is mutual
+                    reached |= {m ^ (1 << l) for m in reached}
+                assert reached == set(range(N))               # after L steps every node contributed
+                with pytest.raises(rar.RarError):
+                    rar.rar_plan_peer(plan, p, L)
+            with pytest.raises(rar.RarError):
+                rar.rar_plan_peer(plan, P, 0)
+            rar.rar_plan_free(plan)
+
+
+@pytest.mark.parametrize("dtype,per_vec", [(0, 8), (1, 4)])
+def test_chunk_partition(dtype, per_vec):
+    for G in (1, 2, 3, 4, 8):
+        for n in (1, 2, 7, 8, 9, 31, 32, 33, 1000, 4096, 65536, 65537, 1048576):
+            plan = rar.rar_plan(G, G, n, dtype)
+            pos = 0
+            for c in range(G):
+                off, length = rar.rar_plan_chunk(plan, c)
+                assert off == pos and off % per_vec == 0 or length == 0
+                pos = off + length
+            assert pos == n
+            full = rar.rar_plan_chunk(plan, 0)[1]
+            assert full == min(n, -(-(-(-n // G)) // per_vec) * per_vec)
+            with pytest.raises(rar.RarError):
+                rar.rar_plan_chunk(plan, G)
+            rar.rar_plan_free(plan)
+
+
+def test_scratch_size_and_tuning():
+    plan = rar.rar_plan(64, 4, 1048576, 0)
+    # S_0..S_L for 64 ranks of 512 KiB each, plus flags and header
+    assert rar.rar_plan_scratch_bytes(plan) >= 5 * 64 * 512 * 1024
+    assert rar.rar_plan_scratch_bytes(plan) <= 5 * 64 * 512 * 1024 + (1 << 20)
+    rar.rar_plan_set_tuning(plan, 8, 16384)
+    assert rar.rar_plan_get_tuning(plan) == (8, 16384)
+    rar.rar_plan_set_tuning(plan, 0, 0)
+    for bad in [(-1, 0), (257, 0), (4, 1000), (4, 65536)]:
+        with pytest.raises(rar.RarError) as e:
+            rar.rar_plan_set_tuning(plan, *bad)
+        assert e.value.status == -9
+    rar.rar_plan_set_mode(plan, 0)
+    assert rar.rar_plan_get_mode(plan) == 0
+    with pytest.raises(rar.RarError):
+        rar.rar_plan_set_mode(plan, 3)
+    with pytest.raises(rar.RarError):
+        rar.rar_plan_set_scratch(plan, 0, 1 << 30)
+    rar.rar_plan_free(plan)
+
+
+def test_no_device_gives_an_error_not_a_crash():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    plan = rar.rar_plan(8, 4, 1024, 0)
+    rar.rar_plan_set_scratch(plan, 0x1000, 1 << 30)   # never dereferenced on the host
+    with pytest.raises(rar.RarError) as e:
+        rar.rar_allreduce([0x100000 + 4096 * i for i in range(8)], plan)
+    assert e.value.status == -7
+    rar.rar_plan_free(plan)
