@@ -245,6 +245,49 @@ __device__ __forceinline__ void load_slice(const unsigned char *S, u32 v0, u32 v
     }
 }
 
+// Device-coherent access to a partial buffer that another workgroup (possibly on another XCD,
+// behind another L2) produces or consumes inside the same launch.  The "sc1" cache policy
+// makes each 16-byte store write through to device scope and each load fetch from device
+// scope, so no cache-wide write-back or invalidate is needed around the step barrier.  The
+// buffer descriptor bounds every access to the partial buffer (out-of-range lanes are
+// dropped by the hardware).
+typedef u32 u32x4 __attribute__((ext_vector_type(4)));
+constexpr int kDeviceScope = 16;            // cache-policy bit "sc1"
+constexpr u32 kRawBufferFlags = 0x00020000; // 32-bit raw buffer, no swizzle
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t partial_rsrc(const Shape &s, u32 level, u32 rank) {
+    return __builtin_amdgcn_make_buffer_rsrc(partial_buf(s, level, rank), 0, static_cast<u32>(s.chunk_stride),
+                                             kRawBufferFlags);
+}
+
+template <int U>
+__device__ __forceinline__ void store_slice_coherent(__amdgpu_buffer_rsrc_t S, u32 v0, u32 valid, bool whole,
+                                                     const uint4 (&part)[U]) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const u32 v = v0 + u * kThreads;
+        if (whole || v < valid) {
+            u32x4 t = {part[u].x, part[u].y, part[u].z, part[u].w};
+            __builtin_amdgcn_raw_buffer_store_b128(t, S, v * 16u, 0, kDeviceScope);
+        }
+    }
+}
+
+template <int U>
+__device__ __forceinline__ void load_slice_coherent(__amdgpu_buffer_rsrc_t S, u32 v0, u32 valid, bool whole,
+                                                    uint4 (&out)[U]) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const u32 v = v0 + u * kThreads;
+        if (whole || v < valid) {
+            const u32x4 t = __builtin_amdgcn_raw_buffer_load_b128(S, v * 16u, 0, kDeviceScope);
+            out[u] = make_uint4(t.x, t.y, t.z, t.w);
+        } else {
+            out[u] = make_uint4(0u, 0u, 0u, 0u);
+        }
+    }
+}
+
 // ---- step barrier (Algorithm 1: "wait until flag(dst_q) == seq") ---------------------------
 //
 // One 32-bit flag per (step buffer, rank, workgroup slot).  The value is a trip counter that
@@ -256,20 +299,18 @@ __device__ __forceinline__ u32 *flag_ptr(const Shape &s, u32 level, u32 rank, u3
     return flags + (static_cast<u64>(level) * s.P + rank) * kMaxWorkgroupsPerRank + slot;
 }
 
-// All of the workgroup's stores to S are made visible device-wide, then the flag is raised.
+// The workgroup's stores to S were issued at device scope; once every wave has seen them
+// complete, thread 0 raises the flag (also at device scope).
 __device__ __forceinline__ void publish(u32 *flag, u32 value) {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    __builtin_amdgcn_s_waitcnt(0);  // this wave's stores have been accepted by its L2
+    __builtin_amdgcn_s_waitcnt(0);  // this wave's write-through stores have completed
     __syncthreads();
-    if (threadIdx.x == 0) {
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");  // write the L2's dirty lines back
-        __builtin_amdgcn_s_waitcnt(0);                      // ... and wait until that is done
-        __hip_atomic_store(flag, value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
+    if (threadIdx.x == 0) __hip_atomic_store(flag, value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // Thread 0 polls; the wait is bounded by wall-clock time and by the shared status word, so
-// every workgroup leaves the kernel even if a peer never arrives.
+// every workgroup leaves the kernel even if a peer never arrives.  The loads of S that follow
+// are device-scope loads, so nothing has to be invalidated here.
 __device__ __forceinline__ void wait_for(const Shape &s, const u32 *flag, u32 expect, bool &gave_up) {
     if (threadIdx.x == 0) {
         if (!gave_up) {
@@ -292,8 +333,6 @@ __device__ __forceinline__ void wait_for(const Shape &s, const u32 *flag, u32 ex
         }
     }
     __syncthreads();
-    // every wave drops stale L1/L2 lines itself, in program order before its own loads
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
 }
 
 // Workgroup index -> (node, chunk, slot).  Workgroups are dealt to the 8 XCDs round-robin by
@@ -348,7 +387,7 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(RankPtrs bufs, Shape s)
         uint4 part[U];
         if (DATA) reduce_scatter_slice<DT, GT, U>(bufs, s, r_n, c, v0, valid, whole, part);
         if (s.L) {
-            if (DATA) store_slice<U>(partial_buf(s, 0, p), v0, valid, whole, part);
+            if (DATA) store_slice_coherent<U>(partial_rsrc(s, 0, p), v0, valid, whole, part);
             publish(flag_ptr(s, 0, p, w), ticket);
         }
         for (u32 l = 0; l < s.L; ++l) {
@@ -356,12 +395,12 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(RankPtrs bufs, Shape s)
             wait_for(s, flag_ptr(s, l, peer, w), ticket, gave_up);
             if (DATA) {
                 uint4 got[U];
-                load_slice<U>(partial_buf(s, l, peer), v0, valid, whole, got);
+                load_slice_coherent<U>(partial_rsrc(s, l, peer), v0, valid, whole, got);
 #pragma unroll
                 for (int u = 0; u < U; ++u) part[u] = combine<DT>(got[u], part[u]);
             }
             if (l + 1 < s.L) {
-                if (DATA) store_slice<U>(partial_buf(s, l + 1, p), v0, valid, whole, part);
+                if (DATA) store_slice_coherent<U>(partial_rsrc(s, l + 1, p), v0, valid, whole, part);
                 publish(flag_ptr(s, l + 1, p, w), ticket);
             }
         }

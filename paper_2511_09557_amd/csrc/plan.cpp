@@ -34,6 +34,8 @@ int make_geometry(int P, int G, size_t n, int dtype, Geometry *geo) {
     // Vector indices inside a chunk, and G*chunk_vecs over a message, are 32-bit in the kernels.
     if (g.chunk_vecs * static_cast<size_t>(G) >= (static_cast<size_t>(1) << 31)) return RAR_ERR_LIMIT;
     g.chunk_stride = round_up(g.chunk_vecs * 16, kAlign);
+    // A partial buffer is addressed through a buffer descriptor with 32-bit byte offsets.
+    if (g.chunk_stride >= (static_cast<size_t>(1) << 32)) return RAR_ERR_LIMIT;
     g.flags_offset = kHeaderBytes;
     // One flag per (step buffer l < L, rank, workgroup slot); S_L is never exchanged.
     g.flags_bytes = round_up(static_cast<size_t>(L > 0 ? L : 1) * P * kMaxWorkgroupsPerRank * 4, kAlign);
