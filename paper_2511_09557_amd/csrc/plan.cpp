@@ -72,11 +72,15 @@ Tuning resolve_tuning(const rar_plan_t &plan, const long *max_resident) {
         t.unroll = static_cast<int>(plan.user_C_s / (static_cast<size_t>(kThreads) * 16));
         index = t.unroll == 1 ? 0 : t.unroll == 2 ? 1 : t.unroll == 4 ? 2 : 3;
     } else {
-        // Smallest trip size that lets every slice have a workgroup of its own.
-        t.unroll = 8;
-        for (int i = 0; i < 4; ++i) {
-            if (slices(1 << i) <= align_down(cap_for(i))) { t.unroll = 1 << i; index = i; break; }
-        }
+        // 16 KiB trips (4 vectors per thread) amortise the step barriers best on MI355X; take
+        // smaller trips only while the grid would leave most of the 256 compute units idle.
+        index = 2;
+        auto grid = [&](int i) {
+            const long per_rank = slices(1 << i) < cap_for(i) ? slices(1 << i) : cap_for(i);
+            return per_rank * g.P;
+        };
+        while (index > 0 && grid(index) < 256) --index;
+        t.unroll = 1 << index;
     }
     const long cap = cap_for(index);
     const long all = slices(t.unroll);
