@@ -17,6 +17,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
 COPY_PROBE_BYTES = 256 << 20  # the known-size copy that rocprof's byte counters are scaled by
+SWEEP_SEED = 20251109 * 1000 + 400
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "fused_kernel_c4_traffic.json")
 
 
@@ -52,17 +53,18 @@ def time_calls(fn, warmup: int, steps: int):
     return time.perf_counter() - t0, e0.elapsed_time(e1)
 
 
-def time_graph(ar, bufs, calls_per_graph: int, warmup: int, replays: int) -> float:
-    """Mean microseconds per all-reduce with `calls_per_graph` calls captured in one HIP graph."""
+def time_graph(enqueue, calls_per_graph: int, warmup: int, replays: int) -> float:
+    """Mean microseconds per call with `calls_per_graph` calls of enqueue(stream) captured in one
+    HIP graph (the paper's micro-benchmark protocol, Section 5: 100 all-reduces per graph)."""
     import torch
     stream = torch.cuda.Stream()
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.stream(stream):
-        ar(bufs, stream)
+        enqueue(stream)                      # eager call first: one-time set-up stays out of the graph
         stream.synchronize()
         with torch.cuda.graph(graph, stream=stream):
             for _ in range(calls_per_graph):
-                ar(bufs, stream)
+                enqueue(stream)
     torch.cuda.synchronize()
     for _ in range(warmup):
         graph.replay()
@@ -109,24 +111,85 @@ def bench_workload(name: str, warmup: int, steps: int, extras: bool):
            "algorithmic_bytes": algorithmic_bytes(w.P, w.G, w.N, w.bytes_per_rank)}
     bufs = device_bufs(x)
     ar = rar.AllReduce(w.P, w.G, w.n, dtype, rar.RAR_MODE_FUSED)
-    wall, ev_ms = time_calls(lambda: ar(bufs), warmup, steps)
+    ar.bind(bufs)
+    wall, ev_ms = time_calls(lambda: ar.launch(), warmup, steps)
     assert ar.status() == 0
     out["fused_us"] = ev_ms * 1000.0 / steps
     out["fused_wall_us"] = wall * 1e6 / steps
     out["tuning"] = dict(zip(("B_s", "C_s"), ar.tuning()))
     if extras:
         ar.set_mode(rar.RAR_MODE_STEPWISE)
-        _, ev = time_calls(lambda: ar(bufs), warmup // 4 + 1, max(steps // 4, 10))
+        _, ev = time_calls(lambda: ar.launch(), warmup // 4 + 1, max(steps // 4, 10))
         out["stepwise_us"] = ev * 1000.0 / max(steps // 4, 10)
         ar.set_mode(rar.RAR_MODE_FUSED)
         _, ev = time_calls(lambda: ar.launch_floor(), warmup, steps)
         out["launch_floor_us"] = ev * 1000.0 / steps
         _, ev = time_calls(lambda: ar.barrier_only(), warmup, steps)
         out["barrier_only_us"] = ev * 1000.0 / steps
-        out["graph100_us"] = time_graph(ar, bufs, 100, 2, 10)
+        # the same three things inside HIP graphs of 100 calls: the device-side cost without
+        # the host's launch rate.  floor = launch only; barrier = flags only; fused = everything
+        out["graph100_us"] = time_graph(lambda st: ar.launch(st), 100, 2, 10)
+        out["graph100_launch_floor_us"] = time_graph(lambda st: ar.launch_floor(st), 100, 2, 10)
+        out["graph100_barrier_only_us"] = time_graph(lambda st: ar.barrier_only(st), 100, 2, 10)
+        ar.set_mode(rar.RAR_MODE_STEPWISE)
+        out["graph100_stepwise_us"] = time_graph(lambda st: ar.launch(st), 100, 2, 10)
+        ar.set_mode(rar.RAR_MODE_FUSED)
+        # the data+flag ("packed") exchange of Section 4.2.2, where the planner offers it
+        try:
+            ar.set_mode(rar.RAR_MODE_FUSED_PACKED)
+        except rar.RarError:
+            out["packed_us"] = out["graph100_packed_us"] = None
+        else:
+            _, ev = time_calls(lambda: ar.launch(), warmup, steps)
+            out["packed_us"] = ev * 1000.0 / steps
+            out["graph100_packed_us"] = time_graph(lambda st: ar.launch(st), 100, 2, 10)
+            out["packed_tuning"] = dict(zip(("B_s", "C_s"), ar.tuning()))
+            ar.set_mode(rar.RAR_MODE_FUSED)
         assert ar.status() == 0
     ar.close()
     return out
+
+
+def sweep(path: str) -> None:
+    """Message-size sweep (8 KiB .. 64 MiB per rank, P in {8,16,32,64,128} with G=4, plus
+    64 = 8x8; bf16 and fp32; N(0,1) values drawn on the device from a seeded generator).
+    Writes one JSON object per point to `path` and prints a table."""
+    import torch
+    import paper_2511_09557_amd as rar
+    gen = torch.Generator(device="cuda:0")
+    rows = []
+    with open(path, "w") as f:
+        for dtype, code, es, tdt in (("bf16", rar.RAR_BF16, 2, torch.bfloat16), ("f32", rar.RAR_F32, 4, torch.float32)):
+            for P, G in ((8, 4), (16, 4), (32, 4), (64, 4), (128, 4), (64, 8)):
+                for lg in range(13, 27):
+                    nbytes = 1 << lg
+                    n = nbytes // es
+                    gen.manual_seed(SWEEP_SEED + lg * 1000 + P * 10 + G)
+                    bufs = [torch.randn(n, device="cuda:0", generator=gen, dtype=torch.float32).to(tdt) for _ in range(P)]
+                    ar = rar.AllReduce(P, G, n, code, rar.RAR_MODE_FUSED)
+                    ar.bind(bufs)
+                    alg = algorithmic_bytes(P, G, P // G, nbytes)
+                    reps = max(5, min(500, int(2e-2 / max(alg / 5e12, 5e-6))))
+                    _, ev = time_calls(lambda: ar.launch(), max(reps // 5, 2), reps)
+                    fused = ev * 1000.0 / reps
+                    graph = time_graph(lambda st: ar.launch(st), 20, 1, max(reps // 20, 2)) if nbytes <= (4 << 20) else None
+                    ar.set_mode(rar.RAR_MODE_STEPWISE)
+                    _, ev = time_calls(lambda: ar.launch(), max(reps // 5, 2), reps)
+                    stepwise = ev * 1000.0 / reps
+                    assert ar.status() == 0
+                    B_s, C_s = ar.tuning()
+                    ar.close()
+                    row = {"dtype": dtype, "P": P, "G": G, "bytes_per_rank": nbytes, "fused_us": fused,
+                           "fused_in_graph_us": graph, "stepwise_us": stepwise, "algorithmic_bytes": alg,
+                           "fused_GBps": alg / (fused * 1e-6) / 1e9, "B_s": B_s, "C_s": C_s}
+                    f.write(json.dumps(row) + "\n")
+                    f.flush()
+                    rows.append(row)
+                    print(f"{dtype:4s} P={P:3d} G={G} {nbytes:9d} B  fused {fused:10.2f} us ({row['fused_GBps']:7.0f} GB/s)"
+                          f"  graph {graph if graph is None else round(graph, 2)}  stepwise {stepwise:10.2f} us  B_s={B_s} C_s={C_s}",
+                          file=sys.stderr, flush=True)
+                    del bufs
+                    torch.cuda.empty_cache()
 
 
 def cpu_baseline(name: str):
@@ -159,6 +222,7 @@ def main() -> int:
     ap.add_argument("--workload", default="c4", choices=["c1", "c2", "c3", "c4"])
     ap.add_argument("--no-extras", action="store_true", help="only the headline workload, fused mode")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--sweep", metavar="OUT.jsonl", help="run the message-size sweep instead and write it to this file")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build emulates all P ranks on ONE GPU; --gpus must be 1 "
@@ -168,6 +232,10 @@ def main() -> int:
     import torch
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     import rar_inputs as ri
+
+    if args.sweep:
+        sweep(args.sweep)
+        return 0
 
     head = bench_workload(args.workload, args.warmup, args.steps, extras=not args.no_extras)
     copy_probe()

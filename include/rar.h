@@ -40,7 +40,11 @@ typedef enum rar_dtype {
 
 typedef enum rar_mode {
     RAR_MODE_STEPWISE = 0, /* one launch per phase: 1 reduce-scatter + L steps + 1 all-gather */
-    RAR_MODE_FUSED = 1     /* one persistent launch; flag-based step barriers (default)      */
+    RAR_MODE_FUSED = 1,    /* one persistent launch; flag-based step barriers (default)      */
+    RAR_MODE_FUSED_PACKED = 2 /* one persistent launch; every 8-byte word exchanged carries 4 bytes of
+                              data and the call's 4-byte sequence number (Section 4.2.2, the
+                              low-latency payload), so a step needs no separate flag and no
+                              workgroup barrier; twice the exchanged bytes; small messages only */
 } rar_mode;
 
 typedef enum rar_status {
@@ -93,9 +97,10 @@ int rar_plan_peer(const rar_plan_t *plan, int rank, int step);
 /* Element range of chunk c (0 <= c < G): *offset and *length (host, both required). */
 int rar_plan_chunk(const rar_plan_t *plan, int c, size_t *offset, size_t *length);
 
-/* Bytes of device scratch rar_allreduce needs: a 256-byte header (status word), the step
- * barrier flags, and the per-step partial buffers S_0..S_L of every rank (Section 4.2.1:
- * one buffer per inter-node step, so a rank may run ahead of its peer). */
+/* Bytes of device scratch rar_allreduce needs: a 256-byte header (status word, sequence
+ * number), the step barrier flags, the per-step partial buffers S_0..S_L of every rank
+ * (Section 4.2.1: one buffer per inter-node step, so a rank may run ahead of its peer) and,
+ * for chunks of at most 256 KiB, the per-step data+flag buffers of the packed mode. */
 size_t rar_plan_scratch_bytes(const rar_plan_t *plan);
 
 /* Lend `bytes` of device memory at `scratch` (256-byte aligned, >= rar_plan_scratch_bytes)
@@ -104,7 +109,9 @@ size_t rar_plan_scratch_bytes(const rar_plan_t *plan);
  * header and flags with a fill kernel on its stream. */
 int rar_plan_set_scratch(rar_plan_t *plan, void *scratch, size_t bytes);
 
-/* Execution mode (default RAR_MODE_FUSED).  Both modes produce identical bits. */
+/* Execution mode (default RAR_MODE_FUSED).  All modes produce identical bits.
+ * RAR_MODE_FUSED_PACKED is accepted only while a chunk is at most 256 KiB (RAR_ERR_LIMIT
+ * otherwise); rar_plan_scratch_bytes already includes its buffers for such plans. */
 int rar_plan_set_mode(rar_plan_t *plan, int mode);
 int rar_plan_get_mode(const rar_plan_t *plan);
 

@@ -10,7 +10,7 @@ import os
 from typing import Optional, Sequence
 
 RAR_BF16, RAR_F32 = 0, 1
-RAR_MODE_STEPWISE, RAR_MODE_FUSED = 0, 1
+RAR_MODE_STEPWISE, RAR_MODE_FUSED, RAR_MODE_FUSED_PACKED = 0, 1, 2
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "librar.so")
@@ -193,7 +193,8 @@ class AllReduce:
             rar_plan_free(self.plan)
             self.plan = None
             raise
-        self._ptr_cache = None
+        self._bound = None
+        self._bound_ptrs = None
 
     def _stream(self, stream) -> int:
         import torch
@@ -201,14 +202,26 @@ class AllReduce:
             return torch.cuda.current_stream().cuda_stream
         return stream if isinstance(stream, int) else stream.cuda_stream
 
-    def __call__(self, tensors, stream=None) -> None:
-        """In-place all-reduce of P tensors of n elements each (one per virtual rank)."""
+    def bind(self, tensors) -> None:
+        """Check P tensors (one per virtual rank, n elements each) and keep their addresses, so
+        that later launches marshal nothing per call.  The tensors must stay alive and in place."""
         if len(tensors) != self.P:
             raise ValueError(f"need {self.P} tensors")
         for t in tensors:
             if t.numel() != self.n or not t.is_contiguous() or not t.is_cuda:
                 raise ValueError("each rank's tensor must be a contiguous CUDA tensor of n elements")
-        rar_allreduce([t.data_ptr() for t in tensors], self.plan, self._stream(stream))
+        self._bound = tensors
+        self._bound_ptrs = (ctypes.c_void_p * self.P)(*[t.data_ptr() for t in tensors])
+
+    def launch(self, stream=None) -> None:
+        """In-place all-reduce of the bound tensors."""
+        _check(lib.rar_allreduce(self._bound_ptrs, self.plan, self._stream(stream)), "rar_allreduce")
+
+    def __call__(self, tensors, stream=None) -> None:
+        """In-place all-reduce of P tensors of n elements each (one per virtual rank)."""
+        if tensors is not self._bound:
+            self.bind(tensors)
+        self.launch(stream)
 
     def set_mode(self, mode: int) -> None:
         rar_plan_set_mode(self.plan, mode)

@@ -30,7 +30,9 @@ int ensure_flags(rar_plan_t *plan, hipStream_t stream) {
 int ensure_residency(rar_plan_t *plan) {
     if (plan->have_resident) return RAR_OK;
     for (int i = 0; i < 4; ++i) {
-        int rc = rar::fused_max_resident(plan->geo.dtype, plan->geo.G, 1 << i, &plan->resident[i]);
+        int rc = rar::fused_max_resident(plan->geo.dtype, plan->geo.G, 1 << i, false, &plan->resident[i]);
+        if (rc != RAR_OK) return rc;
+        rc = rar::fused_max_resident(plan->geo.dtype, plan->geo.G, 1 << i, true, &plan->resident_packed[i]);
         if (rc != RAR_OK) return rc;
     }
     plan->have_resident = true;
@@ -38,13 +40,24 @@ int ensure_residency(rar_plan_t *plan) {
 }
 
 // The fused kernel's step barriers need every workgroup of the grid resident at once.
-int fused_tuning(rar_plan_t *plan, Tuning *t) {
+int fused_tuning(rar_plan_t *plan, bool packed, Tuning *t) {
     int rc = ensure_residency(plan);
     if (rc != RAR_OK) return rc;
-    *t = rar::resolve_tuning(*plan, plan->resident);
+    const long *resident = packed ? plan->resident_packed : plan->resident;
+    *t = rar::resolve_tuning(*plan, resident);
     const int index = t->unroll == 1 ? 0 : t->unroll == 2 ? 1 : t->unroll == 4 ? 2 : 3;
-    if (static_cast<long>(plan->geo.P) * t->B_s > plan->resident[index]) return RAR_ERR_LIMIT;
+    if (static_cast<long>(plan->geo.P) * t->B_s > resident[index]) return RAR_ERR_LIMIT;
     return RAR_OK;
+}
+
+// The data+flag buffers must not hold a word whose upper half could equal a sequence number.
+int ensure_packed(rar_plan_t *plan, hipStream_t stream) {
+    if (plan->packed_clean || plan->geo.packed_offset == 0) return RAR_OK;
+    const Geometry &g = plan->geo;
+    int rc = rar::launch_fill_zero(static_cast<unsigned char *>(plan->scratch) + g.packed_offset,
+                                   g.scratch_bytes - g.packed_offset, stream);
+    if (rc == RAR_OK) plan->packed_clean = true;
+    return rc;
 }
 
 }  // namespace
@@ -60,6 +73,7 @@ int rar_plan_status(rar_plan_t *plan, void *stream) {
     if (hipMemcpy(&word, plan->scratch, sizeof word, hipMemcpyDeviceToHost) != hipSuccess) return RAR_ERR_HIP;
     if (word == 0) return RAR_OK;
     plan->flags_clean = false;  // counters of different slots may now disagree: start over
+    plan->packed_clean = false;
     return RAR_ERR_TIMEOUT;
 }
 
@@ -93,18 +107,22 @@ int rar_allreduce(void *const *bufs, rar_plan_t *plan, void *stream) {
     }
     hipStream_t st = as_stream(stream);
     if (plan->mode == RAR_MODE_STEPWISE) return rar::launch_stepwise(*plan, ptrs, st);
+    const bool packed = plan->mode == RAR_MODE_FUSED_PACKED && g.L > 0;
     Tuning t;
-    rc = fused_tuning(plan, &t);
+    rc = fused_tuning(plan, packed, &t);
     if (rc != RAR_OK) return rc;
     rc = ensure_flags(plan, st);
     if (rc != RAR_OK) return rc;
-    return rar::launch_fused(*plan, ptrs, t, true, st);
+    if (!packed) return rar::launch_fused(*plan, ptrs, t, true, st);
+    rc = ensure_packed(plan, st);
+    if (rc != RAR_OK) return rc;
+    return rar::launch_fused_packed(*plan, ptrs, t, st);
 }
 
 int rar_launch_floor(rar_plan_t *plan, void *stream) {
     if (!plan) return RAR_ERR_ARG;
     Tuning t;
-    int rc = fused_tuning(plan, &t);
+    int rc = fused_tuning(plan, plan->mode == RAR_MODE_FUSED_PACKED && plan->geo.L > 0, &t);
     if (rc != RAR_OK) return rc;
     return rar::launch_empty(static_cast<unsigned>(plan->geo.P) * t.B_s, as_stream(stream));
 }
@@ -114,7 +132,7 @@ int rar_barrier_only(rar_plan_t *plan, void *stream) {
     int rc = ensure_scratch(plan);
     if (rc != RAR_OK) return rc;
     Tuning t;
-    rc = fused_tuning(plan, &t);
+    rc = fused_tuning(plan, false, &t);
     if (rc != RAR_OK) return rc;
     hipStream_t st = as_stream(stream);
     rc = ensure_flags(plan, st);

@@ -131,6 +131,8 @@ struct Shape {
     u64 chunk_stride;        // bytes between S buffers
     u64 flags_offset;
     u64 data_offset;
+    u64 packed_offset;       // data+flag buffers of the packed exchange
+    u64 packed_stride;
     u64 wait_ticks;          // step-barrier time limit in 100 MHz ticks
     u32 P, G, N, L;
     u32 chunk_vecs;          // vectors per full chunk
@@ -408,6 +410,127 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(RankPtrs bufs, Shape s)
     }
 }
 
+// ---- the fused schedule with data+flag words (Section 4.2.2, the low-latency payload) -------
+//
+// Every 8-byte word that crosses between ranks carries 4 bytes of data and the 4-byte sequence
+// number of the call, written and read with single 64-bit device-scope accesses, so a word is
+// either old (previous sequence number) or complete.  The receiver polls the data words
+// themselves: no separate flag, no wait for the stores to complete, no workgroup barrier; each
+// wavefront moves on as soon as its own 64 lanes have their words.  Twice the exchanged bytes.
+//
+// Scratch header: word 0 status, word 1 sequence number of the last finished call, word 2
+// count of workgroups that have finished the current call.  All workgroups read word 1 when
+// they start; the last one to finish stores the new number, so a number is never stored
+// before every workgroup of the launch has read the old one.  Keeping it on the device makes
+// the call replayable from a captured graph.
+
+__device__ __forceinline__ u64 *packed_buf(const Shape &s, u32 level, u32 rank) {
+    return reinterpret_cast<u64 *>(s.scratch + s.packed_offset +
+                                   (static_cast<u64>(level) * s.P + rank) * s.packed_stride);
+}
+
+// Word layout inside a slice: [vector-in-thread u][word k of the vector][thread], so that one
+// store or load instruction of a wavefront covers 512 contiguous bytes.
+template <int U>
+__device__ __forceinline__ void store_slice_packed(u64 *buf, u32 slice, u32 v0, u32 valid, bool whole, u32 seq,
+                                                   const uint4 (&part)[U]) {
+    u64 *base = buf + static_cast<u64>(slice) * (kThreads * U * 4) + threadIdx.x;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        if (whole || v0 + u * kThreads < valid) {
+            const u32 d[4] = {part[u].x, part[u].y, part[u].z, part[u].w};
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                __hip_atomic_store(base + (u * 4 + k) * kThreads, (static_cast<u64>(seq) << 32) | d[k],
+                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+}
+
+template <int U>
+__device__ __forceinline__ void load_slice_packed(const Shape &s, const u64 *buf, u32 slice, u32 v0, u32 valid,
+                                                  bool whole, u32 seq, bool &gave_up, uint4 (&out)[U]) {
+    const u64 *base = buf + static_cast<u64>(slice) * (kThreads * U * 4) + threadIdx.x;
+    u32 *status = reinterpret_cast<u32 *>(s.scratch);
+    const u64 t0 = wall_clock64();
+    u32 spins = 0;
+    for (;;) {
+        bool ready = true;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            u32 d[4] = {0u, 0u, 0u, 0u};
+            if (whole || v0 + u * kThreads < valid) {
+                u64 w[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+                    w[k] = __hip_atomic_load(base + (u * 4 + k) * kThreads, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    ready = ready && static_cast<u32>(w[k] >> 32) == seq;
+                    d[k] = static_cast<u32>(w[k]);
+                }
+            }
+            out[u] = make_uint4(d[0], d[1], d[2], d[3]);
+        }
+        if (__all(ready) || gave_up) break;
+        __builtin_amdgcn_s_sleep(1);
+        if ((++spins & 31u) == 0u) {
+            const bool late = wall_clock64() - t0 > s.wait_ticks;  // wave-uniform
+            if (late) __hip_atomic_store(status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (late || __hip_atomic_load(status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) gave_up = true;
+        }
+    }
+}
+
+template <int DT, int GT, int U>
+__global__ __launch_bounds__(kThreads) void fused_packed_kernel(RankPtrs bufs, Shape s) {
+    u32 r_n, c, w;
+    locate(s, blockIdx.x, r_n, c, w);
+    const u32 G = GT ? GT : s.G;
+    const u32 p = r_n * G + c;
+    const u32 valid_vecs = chunk_valid_vecs(s, c);
+    const u64 cbegin = static_cast<u64>(c) * s.chunk_vecs;
+    const u32 whole_vecs = s.full_vecs > cbegin
+                               ? (s.full_vecs - cbegin < valid_vecs ? static_cast<u32>(s.full_vecs - cbegin) : valid_vecs)
+                               : 0u;
+    u32 *header = reinterpret_cast<u32 *>(s.scratch);
+    u32 seq = __hip_atomic_load(header + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u;
+    if (seq == 0u) seq = 1u;  // zero marks a word that was never written
+    bool gave_up = false;
+
+    for (u32 it = 0; it < s.iters; ++it) {
+        const u32 slice = w + it * s.B_s;
+        const u64 first = static_cast<u64>(slice) * (kThreads * U);
+        const u32 v0 = static_cast<u32>(first) + threadIdx.x;
+        const bool whole = first + kThreads * U <= whole_vecs;
+        const u32 valid = first < valid_vecs ? valid_vecs : 0u;
+
+        uint4 part[U];
+        reduce_scatter_slice<DT, GT, U>(bufs, s, r_n, c, v0, valid, whole, part);
+        if (valid != 0u) {  // uniform over the workgroup; a slice past the chunk exchanges nothing
+            if (s.L) store_slice_packed<U>(packed_buf(s, 0, p), slice, v0, valid, whole, seq, part);
+            for (u32 l = 0; l < s.L; ++l) {
+                const u32 peer = (r_n ^ (1u << l)) * G + c;
+                uint4 got[U];
+                load_slice_packed<U>(s, packed_buf(s, l, peer), slice, v0, valid, whole, seq, gave_up, got);
+#pragma unroll
+                for (int u = 0; u < U; ++u) part[u] = combine<DT>(got[u], part[u]);
+                if (l + 1 < s.L) store_slice_packed<U>(packed_buf(s, l + 1, p), slice, v0, valid, whole, seq, part);
+            }
+        }
+        all_gather_slice<DT, GT, U>(bufs, s, r_n, c, v0, valid, whole, part);
+    }
+
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const u32 done = __hip_atomic_fetch_add(header + 2, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (done == gridDim.x - 1u) {
+            __hip_atomic_store(header + 2, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(header + 1, seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+}
+
 // ---- stepwise kernels: one launch per phase, one slice per workgroup -------------------------
 
 struct StepShape {
@@ -505,6 +628,8 @@ static Shape make_shape(const rar_plan_t &plan, const Tuning &t, bool xcd_map) {
     s.chunk_stride = g.chunk_stride;
     s.flags_offset = g.flags_offset;
     s.data_offset = g.data_offset;
+    s.packed_offset = g.packed_offset;
+    s.packed_stride = g.packed_stride;
     s.wait_ticks = plan.wait_limit_us * 100ull;  // the wall clock counts at 100 MHz
     s.P = g.P; s.G = g.G; s.N = g.N; s.L = g.L;
     s.chunk_vecs = static_cast<u32>(g.chunk_vecs);
@@ -542,6 +667,29 @@ static FusedFn pick_fused(int dtype, int G, int unroll, bool data) {
     return data ? pick_group<RAR_F32, true>(G, unroll) : pick_group<RAR_F32, false>(G, unroll);
 }
 
+template <int DT, int GT>
+static FusedFn pick_packed_unroll(int unroll) {
+    switch (unroll) {
+        case 1: return fused_packed_kernel<DT, GT, 1>;
+        case 2: return fused_packed_kernel<DT, GT, 2>;
+        case 4: return fused_packed_kernel<DT, GT, 4>;
+        default: return fused_packed_kernel<DT, GT, 8>;
+    }
+}
+template <int DT>
+static FusedFn pick_packed_group(int G, int unroll) {
+    switch (G) {
+        case 1: return pick_packed_unroll<DT, 1>(unroll);
+        case 2: return pick_packed_unroll<DT, 2>(unroll);
+        case 4: return pick_packed_unroll<DT, 4>(unroll);
+        case 8: return pick_packed_unroll<DT, 8>(unroll);
+        default: return pick_packed_unroll<DT, 0>(unroll);
+    }
+}
+static FusedFn pick_packed(int dtype, int G, int unroll) {
+    return dtype == RAR_BF16 ? pick_packed_group<RAR_BF16>(G, unroll) : pick_packed_group<RAR_F32>(G, unroll);
+}
+
 int device_info(DeviceInfo *out) {
     static DeviceInfo cached[16];
     static bool have[16] = {};
@@ -559,12 +707,12 @@ int device_info(DeviceInfo *out) {
     return RAR_OK;
 }
 
-int fused_max_resident(int dtype, int G, int unroll, long *out) {
+int fused_max_resident(int dtype, int G, int unroll, bool packed, long *out) {
     DeviceInfo info;
     int rc = device_info(&info);
     if (rc != RAR_OK) return rc;
     int per_cu = 0;
-    FusedFn fn = pick_fused(dtype, G, unroll, true);
+    FusedFn fn = packed ? pick_packed(dtype, G, unroll) : pick_fused(dtype, G, unroll, true);
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(fn), kThreads, 0) !=
             hipSuccess || per_cu < 1)
         return RAR_ERR_HIP;
@@ -589,6 +737,16 @@ int launch_fused(const rar_plan_t &plan, const RankPtrs &bufs, const Tuning &t, 
     const Shape s = make_shape(plan, t, pairs % 8 == 0);
     const u32 grid = static_cast<u32>(g.P) * t.B_s;
     FusedFn fn = pick_fused(g.dtype, g.G, t.unroll, data);
+    fn<<<dim3(grid), dim3(kThreads), 0, stream>>>(bufs, s);
+    return check_launch();
+}
+
+int launch_fused_packed(const rar_plan_t &plan, const RankPtrs &bufs, const Tuning &t, hipStream_t stream) {
+    const Geometry &g = plan.geo;
+    const u32 pairs = static_cast<u32>(g.G) * t.B_s;
+    const Shape s = make_shape(plan, t, pairs % 8 == 0);
+    const u32 grid = static_cast<u32>(g.P) * t.B_s;
+    FusedFn fn = pick_packed(g.dtype, g.G, t.unroll);
     fn<<<dim3(grid), dim3(kThreads), 0, stream>>>(bufs, s);
     return check_launch();
 }

@@ -20,10 +20,11 @@ struct DeviceInfo {
 int device_info(DeviceInfo *out);
 
 // Workgroups of the fused kernel (dtype, G, unroll) the current device can hold at once.
-int fused_max_resident(int dtype, int G, int unroll, long *out);
+int fused_max_resident(int dtype, int G, int unroll, bool packed, long *out);
 
 int launch_fill_zero(void *words, size_t bytes, hipStream_t stream);
 int launch_fused(const rar_plan_t &plan, const RankPtrs &bufs, const Tuning &t, bool data, hipStream_t stream);
+int launch_fused_packed(const rar_plan_t &plan, const RankPtrs &bufs, const Tuning &t, hipStream_t stream);
 int launch_stepwise(const rar_plan_t &plan, const RankPtrs &bufs, hipStream_t stream);
 int launch_empty(unsigned grid, hipStream_t stream);
 int launch_combine(void *dst, const void *src, size_t full_vecs, unsigned tail, int dtype, hipStream_t stream);

@@ -41,6 +41,14 @@ int make_geometry(int P, int G, size_t n, int dtype, Geometry *geo) {
     g.flags_bytes = round_up(static_cast<size_t>(L > 0 ? L : 1) * P * kMaxWorkgroupsPerRank * 4, kAlign);
     g.data_offset = g.flags_offset + g.flags_bytes;
     g.scratch_bytes = g.data_offset + static_cast<size_t>(L + 1) * P * g.chunk_stride;
+    // Data+flag buffers for the packed exchange: one per (step l < L, rank), twice a chunk.
+    if (L > 0 && g.chunk_vecs * 16 <= kPackedMaxChunkBytes) {
+        g.packed_offset = g.scratch_bytes;
+        // whole slices of the largest trip (8 vectors per thread): the word layout inside a
+        // slice is strided by thread, so a ragged last slice still spans its full extent
+        g.packed_stride = round_up(g.chunk_vecs, static_cast<size_t>(kThreads) * 8) * 32;
+        g.scratch_bytes = g.packed_offset + static_cast<size_t>(L) * P * g.packed_stride;
+    }
     *geo = g;
     return RAR_OK;
 }
@@ -175,11 +183,15 @@ int rar_plan_set_scratch(rar_plan_t *plan, void *scratch, size_t bytes) {
     plan->scratch = scratch;
     plan->scratch_size = bytes;
     plan->flags_clean = false;
+    plan->packed_clean = false;
     return RAR_OK;
 }
 
 int rar_plan_set_mode(rar_plan_t *plan, int mode) {
-    if (!plan || (mode != RAR_MODE_STEPWISE && mode != RAR_MODE_FUSED)) return RAR_ERR_ARG;
+    if (!plan) return RAR_ERR_ARG;
+    if (mode != RAR_MODE_STEPWISE && mode != RAR_MODE_FUSED && mode != RAR_MODE_FUSED_PACKED) return RAR_ERR_ARG;
+    // N = 1 has no exchange at all: the packed mode is then the plain fused kernel.
+    if (mode == RAR_MODE_FUSED_PACKED && plan->geo.L > 0 && plan->geo.packed_offset == 0) return RAR_ERR_LIMIT;
     plan->mode = mode;
     return RAR_OK;
 }
@@ -197,7 +209,9 @@ int rar_plan_set_tuning(rar_plan_t *plan, int B_s, size_t C_s) {
 
 int rar_plan_get_tuning(const rar_plan_t *plan, int *B_s, size_t *C_s) {
     if (!plan || !B_s || !C_s) return RAR_ERR_ARG;
-    rar::Tuning t = rar::resolve_tuning(*plan, plan->have_resident ? plan->resident : nullptr);
+    const long *resident = !plan->have_resident ? nullptr
+                           : plan->mode == RAR_MODE_FUSED_PACKED ? plan->resident_packed : plan->resident;
+    rar::Tuning t = rar::resolve_tuning(*plan, resident);
     *B_s = t.B_s;
     *C_s = static_cast<size_t>(rar::kThreads) * 16 * t.unroll;
     return RAR_OK;

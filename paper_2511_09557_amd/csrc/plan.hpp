@@ -14,6 +14,9 @@ constexpr int kThreads = 256;           // threads per workgroup of every kernel
 constexpr int kMaxWorkgroupsPerRank = 256;
 constexpr size_t kHeaderBytes = 256;    // scratch header: status word at offset 0
 constexpr size_t kAlign = 256;
+// The fused data+flag exchange doubles the exchanged bytes, so it is offered for small messages
+// only: chunks of at most this many bytes (a 1 MiB message at G = 4).
+constexpr size_t kPackedMaxChunkBytes = 256 * 1024;
 
 inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -29,6 +32,8 @@ struct Geometry {
     size_t flags_offset = 0; // byte offset of the barrier flags in the scratch
     size_t flags_bytes = 0;
     size_t data_offset = 0;  // byte offset of S_0(rank 0)
+    size_t packed_offset = 0;  // byte offset of the data+flag buffers (0 = the plan has none)
+    size_t packed_stride = 0;  // bytes of one data+flag buffer: 2 * chunk bytes, rounded
     size_t scratch_bytes = 0;
 };
 
@@ -43,7 +48,9 @@ struct rar_plan_s {
     void *scratch = nullptr;   // device, borrowed
     size_t scratch_size = 0;
     bool flags_clean = false;  // header + flags zeroed since the last event that invalidated them
+    bool packed_clean = false; // data+flag buffers zeroed (no stale word can match a sequence number)
     long resident[4] = {0, 0, 0, 0};  // cached residency of the fused kernel per unroll 1,2,4,8
+    long resident_packed[4] = {0, 0, 0, 0};  // same for the packed fused kernel
     bool have_resident = false;
 };
 

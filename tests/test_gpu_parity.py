@@ -13,7 +13,7 @@ rar = pytest.importorskip("paper_2511_09557_amd") if torch.cuda.is_available() e
 
 DT = {"bf16": 0, "f32": 1}
 NP = {"bf16": np.uint16, "f32": np.float32}
-MODES = {"stepwise": 0, "fused": 1}
+MODES = {"stepwise": 0, "fused": 1, "packed": 2}
 
 
 def run_gpu(x: np.ndarray, G: int, mode: str, B_s: int = 0, C_s: int = 0, calls: int = 1) -> np.ndarray:
@@ -67,10 +67,18 @@ def test_step_combine_rejects_bad_arguments():
 
 # ---- the five workloads -------------------------------------------------------------------------
 
-@pytest.mark.parametrize("mode", ["stepwise", "fused"])
+@pytest.mark.parametrize("mode", ["stepwise", "fused", "packed"])
 @pytest.mark.parametrize("name", ["c1", "c1_int", "c2", "c3", "c4"])
 def test_workloads_bit_exact(name, mode):
     w = ri.WORKLOADS[name]
+    if mode == "packed" and name == "c4":
+        # a 512 KiB chunk is beyond the packed mode's limit: the planner must say so
+        plan = rar.rar_plan(w.P, w.G, w.n, 0)
+        with pytest.raises(rar.RarError) as e:
+            rar.rar_plan_set_mode(plan, 2)
+        assert e.value.status == -4
+        rar.rar_plan_free(plan)
+        return
     x = ri.make_inputs(w)
     want = oracle.allreduce(x, w.G, threads=8)
     got = run_gpu(x, w.G, mode)
@@ -96,6 +104,7 @@ def test_sweep_small_sizes_bit_exact(P, G, dtype):
         x = ri.make_inputs(w)
         want = oracle.allreduce(x, G, threads=8)
         assert_same_bits(run_gpu(x, G, "fused"), want, w.name)
+        assert_same_bits(run_gpu(x, G, "packed"), want, w.name + "/packed")
         if nbytes == 64 << 10:
             assert_same_bits(run_gpu(x, G, "stepwise"), want, w.name + "/stepwise")
             ref, mag = oracle.naive_sum_f64(x)
@@ -151,6 +160,8 @@ def test_edge_shapes(P, G, n, dtype):
     want = oracle.allreduce(x, G)
     assert_same_bits(run_gpu(x, G, "fused"), want, "fused")
     assert_same_bits(run_gpu(x, G, "stepwise"), want, "stepwise")
+    assert_same_bits(run_gpu(x, G, "packed"), want, "packed")
+    assert_same_bits(run_gpu(x, G, "packed", B_s=1, C_s=4096), want, "packed, one workgroup per rank")
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
@@ -171,6 +182,7 @@ def test_special_values(dtype):
     want = oracle.allreduce(x, G)
     assert_same_bits(run_gpu(x, G, "fused"), want, "fused")
     assert_same_bits(run_gpu(x, G, "stepwise"), want, "stepwise")
+    assert_same_bits(run_gpu(x, G, "packed"), want, "packed")
 
 
 @pytest.mark.parametrize("B_s,C_s", [(1, 4096), (2, 8192), (3, 4096), (8, 16384), (16, 32768), (256, 4096), (5, 0), (0, 8192)])
@@ -179,6 +191,7 @@ def test_tuning_never_changes_bits(B_s, C_s):
     x = ri.make_inputs(w)
     want = oracle.allreduce(x, w.G, threads=8)
     assert_same_bits(run_gpu(x, w.G, "fused", B_s=B_s, C_s=C_s), want, f"B_s={B_s} C_s={C_s}")
+    assert_same_bits(run_gpu(x, w.G, "packed", B_s=B_s, C_s=C_s), want, f"packed B_s={B_s} C_s={C_s}")
 
 
 def test_repeated_calls_in_place():
@@ -192,6 +205,8 @@ def test_repeated_calls_in_place():
     assert_same_bits(run_gpu(x, w.G, "fused", calls=3), want, "fused x3")
     assert_same_bits(run_gpu(x, w.G, "fused", B_s=2, C_s=4096, calls=3), want, "fused x3, several trips")
     assert_same_bits(run_gpu(x, w.G, "stepwise", calls=3), want, "stepwise x3")
+    assert_same_bits(run_gpu(x, w.G, "packed", calls=3), want, "packed x3")
+    assert_same_bits(run_gpu(x, w.G, "packed", B_s=2, C_s=4096, calls=3), want, "packed x3, several trips")
 
 
 def test_fused_equals_stepwise_under_replay():
@@ -200,6 +215,7 @@ def test_fused_equals_stepwise_under_replay():
     P, G, n = 32, 4, 256 * 1024
     a = rar.AllReduce(P, G, n, 0, 1)
     b = rar.AllReduce(P, G, n, 0, 0)
+    c = rar.AllReduce(P, G, n, 0, 2)
     gen = torch.Generator(device="cuda:0")
     gen.manual_seed(1234)
     print("[gpu] replay stress", flush=True)
@@ -207,24 +223,30 @@ def test_fused_equals_stepwise_under_replay():
         src = torch.randn(P, n, device="cuda:0", generator=gen).to(torch.bfloat16)
         xa = [src[p].clone() for p in range(P)]
         xb = [src[p].clone() for p in range(P)]
+        xc = [src[p].clone() for p in range(P)]
         if it % 3 == 1:
             a.set_tuning(4, 8192)
+            c.set_tuning(4, 8192)
         elif it % 3 == 2:
             a.set_tuning(0, 0)
+            c.set_tuning(0, 0)
         a(xa)
         b(xb)
+        c(xc)
         for p in range(P):
             assert torch.equal(xa[p].view(torch.int16), xb[0].view(torch.int16)), (it, p)
-    assert a.status() == 0
-    a.close(), b.close()
+            assert torch.equal(xc[p].view(torch.int16), xb[0].view(torch.int16)), ("packed", it, p)
+    assert a.status() == 0 and c.status() == 0
+    a.close(), b.close(), c.close()
 
 
-def test_graph_replay():
+@pytest.mark.parametrize("mode", ["fused", "packed"])
+def test_graph_replay(mode):
     """The fused call inside a HIP graph, replayed with eager work in between."""
     w = ri.WORKLOADS["c2"]
     x = ri.make_inputs(w)
     want = oracle.allreduce(x, w.G, threads=8)
-    ar = rar.AllReduce(w.P, w.G, w.n, 0, 1)
+    ar = rar.AllReduce(w.P, w.G, w.n, 0, MODES[mode])
     src = to_device(x)
     bufs = [t.clone() for t in src]
     ar(bufs)                                   # eager warm-up: clears the flags once
@@ -249,13 +271,14 @@ def test_graph_replay():
     ar.close()
 
 
-def test_wait_limit_ends_every_workgroup():
+@pytest.mark.parametrize("mode", ["fused", "packed"])
+def test_wait_limit_ends_every_workgroup(mode):
     """A 1-tick wait limit makes waits give up instead of spinning: the kernel must still
     finish, report the time-out, and the plan must work again afterwards."""
     w = ri.WORKLOADS["c3"]
     x = ri.make_inputs(w)
     want = oracle.allreduce(x, w.G, threads=8)
-    ar = rar.AllReduce(w.P, w.G, w.n, 0, 1)
+    ar = rar.AllReduce(w.P, w.G, w.n, 0, MODES[mode])
     ar.set_tuning(2, 4096)                     # many trips, so some wait is certain to be pending
     bufs = to_device(x)
     rar.rar_plan_set_wait_limit_us(ar.plan, 1)

@@ -108,6 +108,14 @@ def test_scratch_size_and_tuning():
     assert rar.rar_plan_get_mode(plan) == 0
     with pytest.raises(rar.RarError):
         rar.rar_plan_set_mode(plan, 3)
+    with pytest.raises(rar.RarError) as e:          # 512 KiB chunks: too large for the packed mode
+        rar.rar_plan_set_mode(plan, 2)
+    assert e.value.status == -4
+    small = rar.rar_plan(32, 4, 524288, 0)
+    rar.rar_plan_set_mode(small, 2)
+    # S_0..S_3 (4 x 32 x 256 KiB) + data+flag buffers (3 x 32 x 512 KiB) + flags + header
+    assert rar.rar_plan_scratch_bytes(small) >= (4 + 6) * 32 * 256 * 1024
+    rar.rar_plan_free(small)
     with pytest.raises(rar.RarError):
         rar.rar_plan_set_scratch(plan, 0, 1 << 30)
     rar.rar_plan_free(plan)
