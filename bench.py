@@ -192,6 +192,55 @@ def sweep(path: str) -> None:
                     torch.cuda.empty_cache()
 
 
+def sensitivity(path: str) -> None:
+    """B_s x C_s sensitivity (the paper's Appendix "Impact of Chunk Size and Block Size", Table 5:
+    a 1024 KB message on 16 GPUs), also for the four workloads, as microseconds per all-reduce
+    inside HIP graphs of 100 calls, plus what rar_autotune picks.  Writes a markdown report."""
+    import torch
+    import paper_2511_09557_amd as rar
+    cases = [("table5-shape: 1024 KiB, P=16 (G=4, N=4)", 16, 4, 524288)]
+    import rar_inputs as ri
+    for name in ("c1", "c2", "c3", "c4"):
+        w = ri.WORKLOADS[name]
+        cases.append((f"{name}: {w.bytes_per_rank >> 10} KiB, P={w.P} (G={w.G}, N={w.N})", w.P, w.G, w.n))
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(SWEEP_SEED + 77)
+    lines = ["# B_s / C_s sensitivity of the fused all-reduce on one MI355X (bf16)", "",
+             "command: `python3 bench.py --sensitivity <this file>`; microseconds per all-reduce, mean over",
+             "10 replays of a HIP graph holding 100 calls; `-` = B_s beyond what the message or the device's",
+             "residency allows (the launch clamps it, so the column to the left already shows that case).", ""]
+    for title, P, G, n in cases:
+        bufs = [torch.randn(n, device="cuda:0", generator=gen).to(torch.bfloat16) for _ in range(P)]
+        ar = rar.AllReduce(P, G, n, rar.RAR_BF16, rar.RAR_MODE_FUSED)
+        ar.bind(bufs)
+        lines += [f"## {title}", "", "| C_s \\ B_s | " + " | ".join(str(b) for b in (1, 2, 4, 8, 16, 32, 64)) + " |",
+                  "|---|" + "---|" * 7]
+        for C_s in (4096, 8192, 16384, 32768):
+            row, seen = [], set()
+            for B_s in (1, 2, 4, 8, 16, 32, 64):
+                ar.set_tuning(B_s, C_s)
+                eff = ar.tuning()[0]
+                if eff in seen:
+                    row.append("-")
+                    continue
+                seen.add(eff)
+                row.append(f"{time_graph(lambda st: ar.launch(st), 100, 1, 10):.2f}")
+            lines.append(f"| {C_s} | " + " | ".join(row) + " |")
+        ar.set_tuning(0, 0)
+        default = ar.tuning()
+        d_us = time_graph(lambda st: ar.launch(st), 100, 1, 10)
+        best = ar.autotune(bufs, calls=50)
+        tuned = ar.tuning()
+        t_us = time_graph(lambda st: ar.launch(st), 100, 1, 10)
+        lines += ["", f"built-in choice (B_s, C_s) = {default}: {d_us:.2f} us; rar_autotune picks {tuned}: {t_us:.2f} us "
+                  f"(its own eager measurement: {best:.2f} us)", ""]
+        assert ar.status() == 0
+        ar.close()
+        print(title, "done", file=sys.stderr, flush=True)
+    with open(path, "w") as f:
+        f.write("\n".join(lines) + "\n")
+
+
 def cpu_baseline(name: str):
     """The oracle as it stands, on the host cores of this machine, on one whole all-reduce of the
     workload (repeated until about 10 s have passed)."""
@@ -222,6 +271,7 @@ def main() -> int:
     ap.add_argument("--workload", default="c4", choices=["c1", "c2", "c3", "c4"])
     ap.add_argument("--no-extras", action="store_true", help="only the headline workload, fused mode")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--sensitivity", metavar="OUT.md", help="run the B_s x C_s sensitivity study instead and write it to this file")
     ap.add_argument("--sweep", metavar="OUT.jsonl", help="run the message-size sweep instead and write it to this file")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -235,6 +285,9 @@ def main() -> int:
 
     if args.sweep:
         sweep(args.sweep)
+        return 0
+    if args.sensitivity:
+        sensitivity(args.sensitivity)
         return 0
 
     head = bench_workload(args.workload, args.warmup, args.steps, extras=not args.no_extras)

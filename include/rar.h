@@ -156,6 +156,16 @@ int rar_step_combine(void *dst, const void *src, size_t chunk, size_t n, int dty
  */
 int rar_allreduce(void *const *bufs, rar_plan_t *plan, void *stream);
 
+/* Pick B_s and C_s by measurement (the paper tunes both once per message size and node count,
+ * Section 4.2.1, and leaves heuristics to future work).  Runs the fused all-reduce of the
+ * plan's current mode on `bufs` (same contract as rar_allreduce; the buffers are overwritten
+ * with repeated sums, so pass buffers whose contents do not matter) with every candidate pair,
+ * `calls` timed calls each (>= 1) after two warm-up calls, timed with HIP events on `stream`,
+ * and leaves the fastest pair set in the plan as if by rar_plan_set_tuning.  Synchronises the
+ * stream.  *best_us (host, may be NULL) receives the winner's mean microseconds per call.
+ * Stepwise mode has nothing to tune: RAR_ERR_ARG. */
+int rar_autotune(void *const *bufs, rar_plan_t *plan, void *stream, int calls, double *best_us);
+
 /* ---- measurement aids (used by the benchmark, no effect on results) -----------------------
  *
  * rar_launch_floor: enqueue an empty kernel with the grid and block size the plan's fused

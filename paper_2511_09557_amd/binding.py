@@ -49,6 +49,7 @@ def _load() -> ctypes.CDLL:
         "rar_plan_status": (ci, [vp, vp]),
         "rar_step_combine": (ci, [vp, vp, sz, sz, ci, vp]),
         "rar_allreduce": (ci, [ctypes.POINTER(vp), vp, vp]),
+        "rar_autotune": (ci, [ctypes.POINTER(vp), vp, vp, ci, ctypes.POINTER(ctypes.c_double)]),
         "rar_launch_floor": (ci, [vp, vp]),
         "rar_barrier_only": (ci, [vp, vp]),
         "rar_copy_probe": (ci, [vp, vp, sz, vp]),
@@ -65,7 +66,7 @@ EXPORTS = ["rar_version", "rar_strerror", "rar_plan", "rar_plan_free", "rar_plan
            "rar_plan_scratch_bytes", "rar_plan_set_scratch", "rar_plan_set_mode",
            "rar_plan_get_mode", "rar_plan_set_tuning", "rar_plan_get_tuning",
            "rar_plan_set_wait_limit_us", "rar_plan_status", "rar_step_combine", "rar_allreduce",
-           "rar_launch_floor", "rar_barrier_only", "rar_copy_probe"]
+           "rar_autotune", "rar_launch_floor", "rar_barrier_only", "rar_copy_probe"]
 
 
 def _check(status: int, where: str) -> int:
@@ -162,6 +163,14 @@ def rar_allreduce(buf_ptrs: Sequence[int], plan: int, stream: int = 0) -> None:
     _check(lib.rar_allreduce(arr, plan, stream), "rar_allreduce")
 
 
+def rar_autotune(buf_ptrs: Sequence[int], plan: int, stream: int = 0, calls: int = 20) -> float:
+    """Returns the winner's mean microseconds per call; the plan keeps the winning B_s, C_s."""
+    arr = (ctypes.c_void_p * len(buf_ptrs))(*buf_ptrs)
+    best = ctypes.c_double()
+    _check(lib.rar_autotune(arr, plan, stream, calls, ctypes.byref(best)), "rar_autotune")
+    return best.value
+
+
 def rar_launch_floor(plan: int, stream: int = 0) -> None:
     _check(lib.rar_launch_floor(plan, stream), "rar_launch_floor")
 
@@ -231,6 +240,14 @@ class AllReduce:
 
     def tuning(self):
         return rar_plan_get_tuning(self.plan)
+
+    def autotune(self, tensors, calls: int = 20, stream=None) -> float:
+        """Measure the candidate (B_s, C_s) pairs on `tensors` (overwritten) and keep the fastest."""
+        self.bind(tensors)
+        best = ctypes.c_double()
+        _check(lib.rar_autotune(self._bound_ptrs, self.plan, self._stream(stream), calls, ctypes.byref(best)),
+               "rar_autotune")
+        return best.value
 
     def status(self, stream=None) -> int:
         return rar_plan_status(self.plan, self._stream(stream))

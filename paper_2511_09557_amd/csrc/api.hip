@@ -119,6 +119,62 @@ int rar_allreduce(void *const *bufs, rar_plan_t *plan, void *stream) {
     return rar::launch_fused_packed(*plan, ptrs, t, st);
 }
 
+int rar_autotune(void *const *bufs, rar_plan_t *plan, void *stream, int calls, double *best_us) {
+    if (!bufs || !plan || calls < 1) return RAR_ERR_ARG;
+    if (plan->mode == RAR_MODE_STEPWISE) return RAR_ERR_ARG;
+    int rc = ensure_residency(plan);
+    if (rc != RAR_OK) return rc;
+    const bool packed = plan->mode == RAR_MODE_FUSED_PACKED && plan->geo.L > 0;
+    const long *resident = packed ? plan->resident_packed : plan->resident;
+    hipStream_t st = as_stream(stream);
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess) return RAR_ERR_HIP;
+    if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return RAR_ERR_HIP; }
+
+    const int keep_B = plan->user_B_s;
+    const size_t keep_C = plan->user_C_s;
+    int best_B = keep_B;
+    size_t best_C = keep_C;
+    double best = -1.0;
+    rc = RAR_OK;
+    for (int i = 0; i < 4 && rc == RAR_OK; ++i) {
+        const size_t C_s = static_cast<size_t>(rar::kThreads) * 16 * (1u << i);
+        plan->user_C_s = C_s;
+        plan->user_B_s = 0;
+        const Tuning widest = rar::resolve_tuning(*plan, resident);
+        int last = -1;
+        // the widest grid that fits, then halves of it while a rank keeps at least one workgroup
+        for (int B_s = widest.B_s; B_s >= 1 && rc == RAR_OK; B_s /= 2) {
+            plan->user_B_s = B_s;
+            const Tuning t = rar::resolve_tuning(*plan, resident);
+            if (t.B_s == last) continue;
+            last = t.B_s;
+            for (int k = 0; k < 2 && rc == RAR_OK; ++k) rc = rar_allreduce(bufs, plan, stream);
+            if (rc != RAR_OK) break;
+            if (hipEventRecord(e0, st) != hipSuccess) { rc = RAR_ERR_HIP; break; }
+            for (int k = 0; k < calls && rc == RAR_OK; ++k) rc = rar_allreduce(bufs, plan, stream);
+            if (rc != RAR_OK) break;
+            float ms = 0.f;
+            if (hipEventRecord(e1, st) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+                hipEventElapsedTime(&ms, e0, e1) != hipSuccess) { rc = RAR_ERR_HIP; break; }
+            const double us = static_cast<double>(ms) * 1000.0 / calls;
+            if (best < 0.0 || us < best) { best = us; best_B = t.B_s; best_C = C_s; }
+            if (static_cast<long>(t.B_s) * plan->geo.P <= 64) break;  // narrower grids only get slower
+        }
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (rc != RAR_OK || best < 0.0) {
+        plan->user_B_s = keep_B;
+        plan->user_C_s = keep_C;
+        return rc != RAR_OK ? rc : RAR_ERR_HIP;
+    }
+    plan->user_B_s = best_B;
+    plan->user_C_s = best_C;
+    if (best_us) *best_us = best;
+    return RAR_OK;
+}
+
 int rar_launch_floor(rar_plan_t *plan, void *stream) {
     if (!plan) return RAR_ERR_ARG;
     Tuning t;

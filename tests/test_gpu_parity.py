@@ -194,6 +194,26 @@ def test_tuning_never_changes_bits(B_s, C_s):
     assert_same_bits(run_gpu(x, w.G, "packed", B_s=B_s, C_s=C_s), want, f"packed B_s={B_s} C_s={C_s}")
 
 
+@pytest.mark.parametrize("mode", ["fused", "packed"])
+def test_autotune_keeps_bits(mode):
+    w = ri.WORKLOADS["c2"]
+    x = ri.make_inputs(w)
+    want = oracle.allreduce(x, w.G, threads=8)
+    ar = rar.AllReduce(w.P, w.G, w.n, 0, MODES[mode])
+    print(f"[gpu] autotune {mode}", flush=True)
+    best = ar.autotune(to_device(x), calls=5)
+    B_s, C_s = ar.tuning()
+    assert best > 0 and B_s >= 1 and C_s in (4096, 8192, 16384, 32768)
+    bufs = to_device(x)
+    ar(bufs)
+    assert ar.status() == 0
+    assert_same_bits(to_host(bufs, x.dtype), want, f"after autotune ({B_s}, {C_s})")
+    ar.set_mode(0)
+    with pytest.raises(rar.RarError):
+        ar.autotune(bufs, calls=1)
+    ar.close()
+
+
 def test_repeated_calls_in_place():
     """Three chained in-place calls; flags are counters that are never cleared in between."""
     w = ri.WORKLOADS["c1"]
