@@ -262,27 +262,29 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t partial_rsrc(const Shape &s, u
                                              kRawBufferFlags);
 }
 
+// s0 = where in the partial buffer this thread's first vector lives (the slice's own place, or
+// the workgroup's ring slot); v0 / valid / whole say which of the thread's vectors exist.
 template <int U>
-__device__ __forceinline__ void store_slice_coherent(__amdgpu_buffer_rsrc_t S, u32 v0, u32 valid, bool whole,
+__device__ __forceinline__ void store_slice_coherent(__amdgpu_buffer_rsrc_t S, u32 s0, u32 v0, u32 valid, bool whole,
                                                      const uint4 (&part)[U]) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const u32 v = v0 + u * kThreads;
         if (whole || v < valid) {
             u32x4 t = {part[u].x, part[u].y, part[u].z, part[u].w};
-            __builtin_amdgcn_raw_buffer_store_b128(t, S, v * 16u, 0, kDeviceScope);
+            __builtin_amdgcn_raw_buffer_store_b128(t, S, (s0 + u * kThreads) * 16u, 0, kDeviceScope);
         }
     }
 }
 
 template <int U>
-__device__ __forceinline__ void load_slice_coherent(__amdgpu_buffer_rsrc_t S, u32 v0, u32 valid, bool whole,
+__device__ __forceinline__ void load_slice_coherent(__amdgpu_buffer_rsrc_t S, u32 s0, u32 v0, u32 valid, bool whole,
                                                     uint4 (&out)[U]) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const u32 v = v0 + u * kThreads;
         if (whole || v < valid) {
-            const u32x4 t = __builtin_amdgcn_raw_buffer_load_b128(S, v * 16u, 0, kDeviceScope);
+            const u32x4 t = __builtin_amdgcn_raw_buffer_load_b128(S, (s0 + u * kThreads) * 16u, 0, kDeviceScope);
             out[u] = make_uint4(t.x, t.y, t.z, t.w);
         } else {
             out[u] = make_uint4(0u, 0u, 0u, 0u);
@@ -385,11 +387,19 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(RankPtrs bufs, Shape s)
         const bool whole = first + kThreads * U <= whole_vecs;
         const u32 valid = first < valid_vecs ? valid_vecs : 0u;  // slices past the chunk do nothing
         const u32 ticket = base + it + 1u;
+        // Where the slice lives in a partial buffer.  With one or two trips every slice has its
+        // own place.  With three or more, a workgroup alternates between two places of its own
+        // (2*B_s*C_s bytes per buffer, which is less than a chunk then): a place is rewritten
+        // two trips later, and by then its reader is done with it, because this workgroup has
+        // since waited for that reader's next trip at the same step, which the reader starts
+        // only after finishing the trip in which it read the place.  The smaller footprint keeps
+        // the exchange inside the memory-side cache however long the message is.
+        const u32 s0 = s.iters >= 3u ? (w * 2u + (it & 1u)) * (kThreads * U) + threadIdx.x : v0;
 
         uint4 part[U];
         if (DATA) reduce_scatter_slice<DT, GT, U>(bufs, s, r_n, c, v0, valid, whole, part);
         if (s.L) {
-            if (DATA) store_slice_coherent<U>(partial_rsrc(s, 0, p), v0, valid, whole, part);
+            if (DATA) store_slice_coherent<U>(partial_rsrc(s, 0, p), s0, v0, valid, whole, part);
             publish(flag_ptr(s, 0, p, w), ticket);
         }
         for (u32 l = 0; l < s.L; ++l) {
@@ -397,12 +407,12 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(RankPtrs bufs, Shape s)
             wait_for(s, flag_ptr(s, l, peer, w), ticket, gave_up);
             if (DATA) {
                 uint4 got[U];
-                load_slice_coherent<U>(partial_rsrc(s, l, peer), v0, valid, whole, got);
+                load_slice_coherent<U>(partial_rsrc(s, l, peer), s0, v0, valid, whole, got);
 #pragma unroll
                 for (int u = 0; u < U; ++u) part[u] = combine<DT>(got[u], part[u]);
             }
             if (l + 1 < s.L) {
-                if (DATA) store_slice_coherent<U>(partial_rsrc(s, l + 1, p), v0, valid, whole, part);
+                if (DATA) store_slice_coherent<U>(partial_rsrc(s, l + 1, p), s0, v0, valid, whole, part);
                 publish(flag_ptr(s, l + 1, p, w), ticket);
             }
         }
