@@ -93,6 +93,25 @@ def test_workloads_bit_exact(name, mode):
     assert rel.max() <= 2.0 ** -7 * np.log2(w.P)
 
 
+@pytest.mark.parametrize("name", ["c3", "c4"])
+def test_workloads_in_the_benchmark_layout(name):
+    """bench.py keeps the P messages as rows of one allocation and binds them once; same here,
+    with the tuning the library picks by itself, two launches, against the oracle applied twice."""
+    w = ri.WORKLOADS[name]
+    x = ri.to_bf16_bits(ri.bf16_bits_to_f32(ri.make_inputs(w)) / 64.0)
+    want = oracle.allreduce(oracle.allreduce(x, w.G, threads=8), w.G, threads=8)
+    whole = torch.from_numpy(x.view(np.int16).copy()).view(torch.bfloat16).to("cuda:0")
+    bufs = [whole[p] for p in range(w.P)]
+    ar = rar.AllReduce(w.P, w.G, w.n, 0, 1)
+    ar.bind(bufs)
+    print(f"[gpu] benchmark layout {name} tuning={ar.tuning()}", flush=True)
+    ar.launch()
+    ar.launch()
+    assert ar.status() == 0
+    assert_same_bits(whole.cpu().view(torch.int16).numpy().view(np.uint16), want, name)
+    ar.close()
+
+
 SWEEP = [(8, 4), (16, 4), (32, 4), (64, 4), (128, 4), (64, 8)]
 
 
@@ -144,6 +163,46 @@ def test_sweep_large_size_sampled():
         for p in range(1, P):
             assert torch.equal(work[p].view(torch.int16), work[0].view(torch.int16))
         ar.close()
+
+
+@pytest.mark.parametrize("P,G,nbytes,dtype", [(128, 4, 4 << 20, "bf16"), (64, 8, 16 << 20, "f32"), (32, 4, 32 << 20, "bf16"),
+                                               (16, 4, 8 << 20, "f32")])
+def test_sweep_large_points_sampled(P, G, nbytes, dtype):
+    """Large sweep points (several trips per workgroup, partial buffers reused): inputs drawn on
+    the device from a seeded torch generator, the oracle checks a strided sample of columns plus
+    both ends and the chunk borders."""
+    tdt, es = (torch.bfloat16, 2) if dtype == "bf16" else (torch.float32, 4)
+    n = nbytes // es
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(ri.SEED_BASE + 450 + P + G)
+    whole = torch.empty(P, n, device="cuda:0", dtype=tdt)
+    for p in range(P):
+        whole[p] = torch.randn(n, device="cuda:0", generator=gen).to(tdt)
+    q = n // G
+    cols = np.unique(np.concatenate([np.arange(0, n, 8191), np.arange(0, 2048), np.arange(n - 2048, n)] +
+                                    [np.arange(c * q - 256, c * q + 256) for c in range(1, G)]))
+    ci = torch.from_numpy(cols).to("cuda:0")
+
+    def sample(t):
+        h = t[:, ci].cpu()
+        return h.view(torch.int16).numpy().view(np.uint16) if dtype == "bf16" else h.numpy()
+
+    want = oracle.allreduce(np.ascontiguousarray(sample(whole)), G, threads=8)
+    for mode in ("fused", "stepwise"):
+        work = whole.clone()
+        bufs = [work[p] for p in range(P)]
+        ar = rar.AllReduce(P, G, n, DT[dtype], MODES[mode])
+        print(f"[gpu] large point P={P} G={G} {nbytes} B {dtype} {mode} tuning={ar.tuning()}", flush=True)
+        ar(bufs)
+        assert ar.status() == 0
+        assert_same_bits(np.ascontiguousarray(sample(work)), want, f"{mode}")
+        first = work[0].view(torch.int16 if dtype == "bf16" else torch.int32)
+        nan = torch.isnan(work[0])
+        for p in range(1, P):
+            other = work[p].view(first.dtype)
+            assert torch.equal(other[~nan], first[~nan])
+        ar.close()
+        del work, bufs
 
 
 # ---- edge cases -------------------------------------------------------------------------------------
