@@ -107,6 +107,7 @@ def measured_traffic(workload: str):
 
 
 def bench_workload(name: str, warmup: int, steps: int, extras: bool):
+    import torch
     import paper_2511_09557_amd as rar
     import rar_inputs as ri
     w = ri.WORKLOADS[name]
@@ -139,6 +140,24 @@ def bench_workload(name: str, warmup: int, steps: int, extras: bool):
         ar.set_mode(rar.RAR_MODE_STEPWISE)
         out["graph100_stepwise_us"] = time_graph(lambda st: ar.launch(st), 100, 2, 10)
         ar.set_mode(rar.RAR_MODE_FUSED)
+        # back-to-back calls versus calls with compute in between (the paper's Appendix B runs a
+        # synthetic matmul between all-reduces): tokens x hidden @ hidden x hidden in bf16, then
+        # the all-reduce; the all-reduce's share is the difference to the matmuls alone
+        hidden = 8192 if w.bytes_per_rank <= (256 << 10) else 16384
+        tokens = max(w.n // hidden, 1)
+        a_mat = torch.randn(tokens, hidden, device="cuda:0", dtype=torch.bfloat16)
+        w_mat = torch.randn(hidden, hidden, device="cuda:0", dtype=torch.bfloat16)
+        o_mat = torch.empty(tokens, hidden, device="cuda:0", dtype=torch.bfloat16)
+        torch.matmul(a_mat, w_mat, out=o_mat)
+        mm = time_graph(lambda st: torch.matmul(a_mat, w_mat, out=o_mat), 100, 2, 10)
+
+        def mm_then_ar(st):
+            torch.matmul(a_mat, w_mat, out=o_mat)
+            ar.launch(st)
+        both = time_graph(mm_then_ar, 100, 2, 10)
+        out["graph100_matmul_us"] = mm
+        out["graph100_interleaved_allreduce_us"] = both - mm
+        del a_mat, w_mat, o_mat
         # the data+flag ("packed") exchange of Section 4.2.2, where the planner offers it
         try:
             ar.set_mode(rar.RAR_MODE_FUSED_PACKED)
@@ -301,7 +320,7 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build emulates all P ranks on ONE GPU; --gpus must be 1 "
-              "(no multi-GPU path exists, see DESIGN.md 'More than one GPU')", file=sys.stderr)
+              "(there is no multi-GPU path: collectives between GPUs are not part of this build)", file=sys.stderr)
         return 2
 
     import torch
