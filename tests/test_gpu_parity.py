@@ -289,32 +289,34 @@ def test_repeated_calls_in_place():
 
 
 def test_fused_equals_stepwise_under_replay():
-    """Stress of the flag protocol: 200 fused calls with fresh inputs, each compared with the
-    stepwise path (which synchronises by kernel boundaries only)."""
+    """Stress of the flag protocol: 1500 fused and packed calls with fresh inputs and changing
+    launch shapes (odd B_s puts the exchanging workgroups on different XCDs), each compared with
+    the stepwise path, which synchronises by kernel boundaries only."""
     P, G, n = 32, 4, 256 * 1024
     a = rar.AllReduce(P, G, n, 0, 1)
     b = rar.AllReduce(P, G, n, 0, 0)
     c = rar.AllReduce(P, G, n, 0, 2)
     gen = torch.Generator(device="cuda:0")
     gen.manual_seed(1234)
+    src = torch.empty(P, n, device="cuda:0", dtype=torch.bfloat16)
+    wa, wb, wc = torch.empty_like(src), torch.empty_like(src), torch.empty_like(src)
+    a.bind([wa[p] for p in range(P)])
+    b.bind([wb[p] for p in range(P)])
+    c.bind([wc[p] for p in range(P)])
     print("[gpu] replay stress", flush=True)
-    for it in range(200):
-        src = torch.randn(P, n, device="cuda:0", generator=gen).to(torch.bfloat16)
-        xa = [src[p].clone() for p in range(P)]
-        xb = [src[p].clone() for p in range(P)]
-        xc = [src[p].clone() for p in range(P)]
-        if it % 3 == 1:
-            a.set_tuning(4, 8192)
-            c.set_tuning(4, 8192)
-        elif it % 3 == 2:
-            a.set_tuning(0, 0)
-            c.set_tuning(0, 0)
-        a(xa)
-        b(xb)
-        c(xc)
-        for p in range(P):
-            assert torch.equal(xa[p].view(torch.int16), xb[0].view(torch.int16)), (it, p)
-            assert torch.equal(xc[p].view(torch.int16), xb[0].view(torch.int16)), ("packed", it, p)
+    shapes = [(0, 0), (4, 8192), (3, 4096), (5, 16384), (1, 32768), (16, 4096)]
+    for it in range(1500):
+        if it % 10 == 0:
+            src.copy_(torch.randn(P, n, device="cuda:0", generator=gen))
+        else:
+            src.mul_(0.5)
+        wa.copy_(src), wb.copy_(src), wc.copy_(src)
+        a.set_tuning(*shapes[(it // 3) % len(shapes)])
+        c.set_tuning(*shapes[(it // 7) % len(shapes)])
+        a.launch(), b.launch(), c.launch()
+        assert torch.equal(wa.view(torch.int16), wb.view(torch.int16)), ("fused", it)
+        assert torch.equal(wc.view(torch.int16), wb.view(torch.int16)), ("packed", it)
+        assert torch.equal(wb[P - 1].view(torch.int16), wb[0].view(torch.int16)), ("ranks differ", it)
     assert a.status() == 0 and c.status() == 0
     a.close(), b.close(), c.close()
 
