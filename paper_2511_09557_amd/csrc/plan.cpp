@@ -13,8 +13,6 @@ static int log2_exact(int v) {
     return (1 << l) == v ? l : -1;
 }
 
-static int gcd(int a, int b) { return b == 0 ? a : gcd(b, a % b); }
-
 int make_geometry(int P, int G, size_t n, int dtype, Geometry *geo) {
     if (!geo || P < 1 || G < 1 || n == 0) return RAR_ERR_ARG;
     if (dtype != RAR_BF16 && dtype != RAR_F32) return RAR_ERR_DTYPE;
@@ -55,10 +53,6 @@ int make_geometry(int P, int G, size_t n, int dtype, Geometry *geo) {
 
 Tuning resolve_tuning(const rar_plan_t &plan, const long *max_resident) {
     const Geometry &g = plan.geo;
-    // Keep G*B_s a multiple of the XCD count when possible, so that the workgroups of all
-    // nodes that exchange one slice can be placed on one XCD (see the launch mapping).
-    const int xcd_step = 8 / gcd(g.G, 8);
-    auto align_down = [&](long w) { return w >= xcd_step ? w / xcd_step * xcd_step : w; };
     auto cap_for = [&](int unroll_index) {
         long cap = kMaxWorkgroupsPerRank;
         if (max_resident && max_resident[unroll_index] > 0) {
@@ -97,11 +91,7 @@ Tuning resolve_tuning(const rar_plan_t &plan, const long *max_resident) {
         want = plan.user_B_s < cap ? plan.user_B_s : cap;
         if (want > all) want = all;
     } else {
-        want = all < cap ? all : cap;
-        const long down = align_down(want);
-        const long up = (want + xcd_step - 1) / xcd_step * xcd_step;
-        // one slice per workgroup if that fits; extra (idle) workgroups are cheaper than a trip
-        want = (up <= cap) ? up : down;
+        want = all < cap ? all : cap;  // one slice per workgroup if the device can hold them all
     }
     if (want < 1) want = 1;
     t.B_s = static_cast<int>(want);
