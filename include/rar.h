@@ -22,6 +22,11 @@
  *   - Nothing here allocates or frees device memory; scratch is lent by the caller.
  *   - A plan is not thread-safe, and two all-reduces on one plan must not overlap in time
  *     (they share the plan's scratch): order them on one stream or use two plans.
+ *   - The fused modes size their grid so that every workgroup is resident at once on an
+ *     otherwise idle device (their step barriers spin).  Work that runs concurrently on other
+ *     streams can take that room away; the waits are bounded (rar_plan_set_wait_limit_us), so
+ *     the call then ends with RAR_ERR_TIMEOUT instead of hanging.  RAR_MODE_STEPWISE has no
+ *     such requirement.
  */
 #ifndef RAR_H
 #define RAR_H
