@@ -42,3 +42,19 @@ def test_native_program_matches_oracle(tmp_path, P, G, n, dtype):
     r = subprocess.run([exe, str(P), str(G), str(n), str(dtype)], capture_output=True, text=True, timeout=100)
     assert r.returncode == 0, r.stdout + r.stderr
     assert "c abi parity ok" in r.stdout
+
+
+def test_planner_and_oracle_under_sanitizers(tmp_path):
+    """plan.cpp (host-only) and the C oracle, built with AddressSanitizer and UBSan, run through
+    every shape and tuning the launchers can see; the program checks that all index ranges the
+    kernels derive from the plan stay inside the buffers the plan sizes."""
+    exe = str(tmp_path / "host_checks")
+    csrc = os.path.join(ROOT, "paper_2511_09557_amd", "csrc")
+    subprocess.run(["g++", "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+                    "-Wall", "-Wextra", "-I", os.path.join(ROOT, "include"), "-I", csrc,
+                    os.path.join(ROOT, "tests", "native", "host_checks.cpp"), os.path.join(csrc, "plan.cpp"),
+                    "-x", "c", os.path.join(ROOT, "oracle", "nvrar_oracle.c"), "-o", exe], check=True)
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1", LD_PRELOAD="")
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=300, env=env)
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert "host checks ok" in r.stdout
