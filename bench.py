@@ -122,6 +122,9 @@ def bench_workload(name: str, warmup: int, steps: int, extras: bool):
     assert ar.status() == 0
     out["fused_us"] = ev_ms * 1000.0 / steps
     out["fused_wall_us"] = wall * 1e6 / steps
+    if extras:  # two more repetitions of the same timed region, to show the spread
+        reps = [out["fused_us"]] + [time_calls(lambda: ar.launch(), 10, steps)[1] * 1000.0 / steps for _ in range(2)]
+        out["fused_us_repetitions"] = reps
     out["tuning"] = dict(zip(("B_s", "C_s"), ar.tuning()))
     if extras:
         ar.set_mode(rar.RAR_MODE_STEPWISE)
@@ -285,6 +288,41 @@ def sensitivity(path: str) -> None:
         f.write("\n".join(lines) + "\n")
 
 
+def hierarchy(path: str) -> None:
+    """Flat versus hierarchical: the same P ranks and message split as G x N in every way that
+    keeps N a power of two.  G = 1 is plain recursive doubling over all ranks (log2 P steps on the
+    whole message), G = P is a single node (no inter-node step); the paper's model (Section 4.3)
+    has log2 N inter-node steps on |M|/G bytes each.  Writes a markdown report."""
+    import torch
+    import paper_2511_09557_amd as rar
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(SWEEP_SEED + 99)
+    lines = ["# Flat versus hierarchical split of the same ranks, one MI355X (bf16)", "",
+             "command: `python3 bench.py --hierarchy <this file>`; fused mode, microseconds per all-reduce inside",
+             "HIP graphs of 100 calls; L = log2 N inter-node steps; algorithmic bytes = P*(2M + (3L+2)M/G).", ""]
+    for P, nbytes in ((16, 256 << 10), (16, 2 << 20), (64, 256 << 10), (64, 2 << 20)):
+        n = nbytes // 2
+        whole = torch.randn(P, n, device="cuda:0", generator=gen).to(torch.bfloat16)
+        bufs = [whole[p] for p in range(P)]
+        lines += [f"## P = {P}, {nbytes >> 10} KiB per rank", "",
+                  "| G | N | L | bytes per step and rank | algorithmic MB | us per all-reduce | algorithmic GB/s |", "|---|---|---|---|---|---|---|"]
+        G = 1
+        while G <= P:
+            N = P // G
+            ar = rar.AllReduce(P, G, n, rar.RAR_BF16, rar.RAR_MODE_FUSED)
+            ar.bind(bufs)
+            us = time_graph(lambda st: ar.launch(st), 100, 2, 10)
+            assert ar.status() == 0
+            ar.close()
+            alg = algorithmic_bytes(P, G, N, nbytes)
+            lines.append(f"| {G} | {N} | {N.bit_length() - 1} | {nbytes // G} | {alg / 1e6:.1f} | {us:.2f} | {alg / us / 1e3:.0f} |")
+            G *= 2
+        lines.append("")
+        print(f"P={P} {nbytes} B done", file=sys.stderr, flush=True)
+    with open(path, "w") as f:
+        f.write("\n".join(lines) + "\n")
+
+
 def cpu_baseline(name: str):
     """The oracle as it stands, on the host cores of this machine, on one whole all-reduce of the
     workload (repeated until about 10 s have passed)."""
@@ -316,6 +354,7 @@ def main() -> int:
     ap.add_argument("--no-extras", action="store_true", help="only the headline workload, fused mode")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--sensitivity", metavar="OUT.md", help="run the B_s x C_s sensitivity study instead and write it to this file")
+    ap.add_argument("--hierarchy", metavar="OUT.md", help="run the flat-versus-hierarchical study instead and write it to this file")
     ap.add_argument("--sweep", metavar="OUT.jsonl", help="run the message-size sweep instead and write it to this file")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -332,6 +371,9 @@ def main() -> int:
         return 0
     if args.sensitivity:
         sensitivity(args.sensitivity)
+        return 0
+    if args.hierarchy:
+        hierarchy(args.hierarchy)
         return 0
 
     head = bench_workload(args.workload, args.warmup, args.steps, extras=not args.no_extras)

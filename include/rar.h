@@ -75,6 +75,10 @@ int rar_version(void);
 /* Static, never-NULL description of a status code. */
 const char *rar_strerror(int status);
 
+/* After a call returned RAR_ERR_HIP: the HIP runtime's own text for the failing status that
+ * the library saw last on the calling thread ("no error" if none).  Never NULL. */
+const char *rar_last_hip_error(void);
+
 /* ---- planner (host only; Algorithm 1's inputs G, N, C_s and its peer rule) ---------------
  *
  * rar_plan: build the schedule for P ranks, G per node, n elements of `dtype` per rank.

@@ -19,10 +19,18 @@ LIB_PATH = os.path.join(_HERE, "librar.so")
 class RarError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
-        super().__init__(f"{where}: {rar_strerror(status)} ({status})")
+        detail = f" [{lib.rar_last_hip_error().decode()}]" if status == -7 else ""
+        super().__init__(f"{where}: {rar_strerror(status)} ({status}){detail}")
 
 
 def _load() -> ctypes.CDLL:
+    # PyTorch wheels bundle their own HIP runtime.  A process that uses both must load torch's
+    # first: with librar.so (and the system runtime it links) loaded before torch, the library's
+    # runtime then finds no device.  torch is optional for the plain rar_* functions.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     if not os.path.exists(LIB_PATH):
         raise ImportError(
             f"{LIB_PATH} is missing: build it with `python -m paper_2511_09557_amd.build` "
@@ -32,6 +40,7 @@ def _load() -> ctypes.CDLL:
     sig = {
         "rar_version": (ci, []),
         "rar_strerror": (ctypes.c_char_p, [ci]),
+        "rar_last_hip_error": (ctypes.c_char_p, []),
         "rar_plan": (ci, [ci, ci, sz, ci, ctypes.POINTER(vp)]),
         "rar_plan_free": (ci, [vp]),
         "rar_plan_ranks": (ci, [vp]),
@@ -61,7 +70,7 @@ def _load() -> ctypes.CDLL:
 
 
 lib = _load()
-EXPORTS = ["rar_version", "rar_strerror", "rar_plan", "rar_plan_free", "rar_plan_ranks",
+EXPORTS = ["rar_version", "rar_strerror", "rar_last_hip_error", "rar_plan", "rar_plan_free", "rar_plan_ranks",
            "rar_plan_nodes", "rar_plan_steps", "rar_plan_peer", "rar_plan_chunk",
            "rar_plan_scratch_bytes", "rar_plan_set_scratch", "rar_plan_set_mode",
            "rar_plan_get_mode", "rar_plan_set_tuning", "rar_plan_get_tuning",

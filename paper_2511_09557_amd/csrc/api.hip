@@ -67,10 +67,10 @@ extern "C" {
 int rar_plan_status(rar_plan_t *plan, void *stream) {
     if (!plan) return RAR_ERR_ARG;
     if (ensure_scratch(plan) != RAR_OK) return RAR_ERR_SCRATCH;
-    if (hipStreamSynchronize(as_stream(stream)) != hipSuccess) return RAR_ERR_HIP;
+    if (rar::note_hip(hipStreamSynchronize(as_stream(stream))) != hipSuccess) return RAR_ERR_HIP;
     if (!plan->flags_clean) return RAR_OK;  // header never initialised: nothing has run
     uint32_t word = 0;
-    if (hipMemcpy(&word, plan->scratch, sizeof word, hipMemcpyDeviceToHost) != hipSuccess) return RAR_ERR_HIP;
+    if (rar::note_hip(hipMemcpy(&word, plan->scratch, sizeof word, hipMemcpyDeviceToHost)) != hipSuccess) return RAR_ERR_HIP;
     if (word == 0) return RAR_OK;
     plan->flags_clean = false;  // counters of different slots may now disagree: start over
     plan->packed_clean = false;
@@ -197,6 +197,8 @@ int rar_barrier_only(rar_plan_t *plan, void *stream) {
     std::memset(&ptrs, 0, sizeof ptrs);
     return rar::launch_fused(*plan, ptrs, t, false, st);
 }
+
+const char *rar_last_hip_error(void) { return rar::last_hip_error_string(); }
 
 int rar_copy_probe(void *dst, const void *src, size_t bytes, void *stream) {
     if (!dst || !src) return RAR_ERR_ARG;

@@ -166,7 +166,8 @@ __device__ __forceinline__ void reduce_scatter_slice(const RankPtrs &bufs, const
     Lanes<DT> acc[U];
     if (whole) {
         // every vector of the slice is a whole vector inside the message: no checks
-        constexpr int GB = GT == 0 ? 1 : (GT * U <= 32 ? GT : (32 / U > 0 ? 32 / U : 1));
+        // buffers loaded per batch: all of them when G is known and small, else four at a time
+        constexpr int GB = GT == 0 ? 4 : (GT * U <= 32 ? GT : (32 / U > 0 ? 32 / U : 1));
         uint4 in[GB][U];
 #pragma unroll
         for (int u = 0; u < U; ++u) acc[u].widen(ld16(bufs.p[r_n * G], mbase + v0 + u * kThreads));
@@ -692,15 +693,23 @@ static FusedFn pick_packed(int dtype, int G, int unroll) {
     return dtype == RAR_BF16 ? pick_packed_group<RAR_BF16>(G, unroll) : pick_packed_group<RAR_F32>(G, unroll);
 }
 
+// The most recent failing HIP status seen by the library on this thread (for rar_last_hip_error).
+static thread_local hipError_t g_last_hip_error = hipSuccess;
+hipError_t note_hip(hipError_t e) {
+    if (e != hipSuccess) g_last_hip_error = e;
+    return e;
+}
+const char *last_hip_error_string() { return g_last_hip_error == hipSuccess ? "no error" : hipGetErrorString(g_last_hip_error); }
+
 int device_info(DeviceInfo *out) {
     static DeviceInfo cached[16];
     static bool have[16] = {};
     int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return RAR_ERR_HIP;
+    if (note_hip(hipGetDevice(&dev)) != hipSuccess) return RAR_ERR_HIP;
     if (dev < 0 || dev >= 16) return RAR_ERR_HIP;
     if (!have[dev]) {
         int cus = 0;
-        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+        if (note_hip(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess || cus < 1)
             return RAR_ERR_HIP;
         cached[dev].compute_units = cus;
         have[dev] = true;
@@ -715,16 +724,20 @@ int fused_max_resident(int dtype, int G, int unroll, bool packed, long *out) {
     if (rc != RAR_OK) return rc;
     int per_cu = 0;
     FusedFn fn = packed ? pick_packed(dtype, G, unroll) : pick_fused(dtype, G, unroll, true);
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(fn), kThreads, 0) !=
+    if (note_hip(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(fn), kThreads, 0)) !=
             hipSuccess || per_cu < 1)
         return RAR_ERR_HIP;
     *out = static_cast<long>(per_cu) * info.compute_units;
     return RAR_OK;
 }
 
-static int check_launch() { return hipGetLastError() == hipSuccess ? RAR_OK : RAR_ERR_HIP; }
+// A launch reports failure through the thread's "last error", which an earlier HIP call of the
+// application may have left set: clear it first, so that what is read afterwards is the launch's.
+static void begin_launch() { (void)hipGetLastError(); }
+static int check_launch() { return note_hip(hipGetLastError()) == hipSuccess ? RAR_OK : RAR_ERR_HIP; }
 
 int launch_fill_zero(void *words, size_t bytes, hipStream_t stream) {
+    begin_launch();
     const u64 count = bytes / 4;
     u64 blocks = (count + kThreads - 1) / kThreads;
     if (blocks > 1024) blocks = 1024;
@@ -734,6 +747,7 @@ int launch_fill_zero(void *words, size_t bytes, hipStream_t stream) {
 }
 
 int launch_fused(const rar_plan_t &plan, const RankPtrs &bufs, const Tuning &t, bool data, hipStream_t stream) {
+    begin_launch();
     const Geometry &g = plan.geo;
     const Shape s = make_shape(plan, t);
     const u32 grid = static_cast<u32>(g.P) * t.B_s;
@@ -743,6 +757,7 @@ int launch_fused(const rar_plan_t &plan, const RankPtrs &bufs, const Tuning &t, 
 }
 
 int launch_fused_packed(const rar_plan_t &plan, const RankPtrs &bufs, const Tuning &t, hipStream_t stream) {
+    begin_launch();
     const Geometry &g = plan.geo;
     const Shape s = make_shape(plan, t);
     const u32 grid = static_cast<u32>(g.P) * t.B_s;
@@ -752,12 +767,14 @@ int launch_fused_packed(const rar_plan_t &plan, const RankPtrs &bufs, const Tuni
 }
 
 int launch_empty(unsigned grid, hipStream_t stream) {
+    begin_launch();
     empty_kernel<<<dim3(grid), dim3(kThreads), 0, stream>>>();
     return check_launch();
 }
 
 template <int DT>
 static int launch_stepwise_t(const rar_plan_t &plan, const RankPtrs &bufs, hipStream_t stream) {
+    begin_launch();
     constexpr int U = 4;
     const Geometry &g = plan.geo;
     Tuning t{1, U, 1};
@@ -783,6 +800,7 @@ int launch_stepwise(const rar_plan_t &plan, const RankPtrs &bufs, hipStream_t st
 }
 
 int launch_combine(void *dst, const void *src, size_t full_vecs, unsigned tail, int dtype, hipStream_t stream) {
+    begin_launch();
     u64 blocks = (full_vecs + kThreads - 1) / kThreads;
     if (blocks == 0) blocks = 1;
     if (blocks > 16384) blocks = 16384;
@@ -797,6 +815,7 @@ int launch_combine(void *dst, const void *src, size_t full_vecs, unsigned tail, 
 }
 
 int launch_copy(void *dst, const void *src, size_t vecs, hipStream_t stream) {
+    begin_launch();
     u64 blocks = (vecs + kThreads - 1) / kThreads;
     if (blocks == 0) return RAR_OK;
     if (blocks > 16384) blocks = 16384;

@@ -19,6 +19,10 @@ struct DeviceInfo {
 
 int device_info(DeviceInfo *out);
 
+// Remember a failing HIP status (returns its argument); text of the last one remembered.
+hipError_t note_hip(hipError_t e);
+const char *last_hip_error_string();
+
 // Workgroups of the fused kernel (dtype, G, unroll) the current device can hold at once.
 int fused_max_resident(int dtype, int G, int unroll, bool packed, long *out);
 
