@@ -393,7 +393,8 @@ def main() -> int:
         "higher_is_better": False,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16 storage, f32 accumulate",
+        "dtype": "f32",             # the additions are binary32; the messages are stored as bf16
+        "storage_dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": f"{args.workload}: P={w.P} (G={w.G} x N={w.N}), {w.bytes_per_rank} B bf16 per rank, fused mode",
                    "tuning": head["tuning"]},
