@@ -33,7 +33,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "nvrar_oracle.c")
 _LIB = os.path.join(_HERE, "libnvrar_oracle.so")
 
-_ERRORS = {-1: "bad argument", -2: "N is not a power of two", -3: "out of memory"}
+_ERRORS = {-1: "bad argument", -3: "out of memory"}
 
 
 def build(force: bool = False) -> str:

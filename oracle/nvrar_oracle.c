@@ -29,6 +29,9 @@
  *   - narrowing to bf16 is round-to-nearest, ties to even; overflow gives +-Inf.
  *   - NaN: only "is NaN" is meaningful; payload and sign of a NaN result are not pinned.
  *
+ * N that is not a power of two is outside the paper; see the comment at sits_out() below for
+ * the extension taken.
+ *
  * The chunk partition (needed when G does not divide n): chunk length is ceil(n/G) rounded
  * up to a whole number of 16-byte groups; chunk c covers [min(c*len,n), min((c+1)*len,n)).
  * Results do not depend on the partition because every element is reduced independently.
@@ -52,7 +55,7 @@ enum { ORACLE_BF16 = 0, ORACLE_F32 = 1 };
 enum {
     ORACLE_OK = 0,
     ORACLE_BAD_ARG = -1,   /* NULL pointer, G < 1, N < 1, n == 0, unknown dtype */
-    ORACLE_BAD_N = -2,     /* N is not a power of two */
+    ORACLE_BAD_N = -2,     /* (unused since N may be any positive number) */
     ORACLE_NO_MEM = -3
 };
 
@@ -97,12 +100,23 @@ static void leave_ieee(unsigned old) {
 #endif
 }
 
-static int log2_exact(int N) { /* -1 unless N is a power of two */
+static int floor_log2(int N) { /* largest L with 2^L <= N */
     int L = 0;
-    if (N < 1) return -1;
-    while ((1 << L) < N) ++L;
-    return (1 << L) == N ? L : -1;
+    while ((2 << L) <= N) ++L;
+    return L;
 }
+
+/* N that is not a power of two.  Algorithm 1 assumes N = 2^L.  For N = 2^L + r (0 < r < 2^L)
+ * this oracle takes the customary extension of recursive doubling (Thakur, Rabenseifner, Gropp,
+ * "Optimization of collective communication operations in MPICH", 2005): the first 2r nodes pair
+ * up as (2i, 2i+1); the even node hands its M' to the odd one and sits out; the 2^L nodes that
+ * remain are renumbered (node 2i+1 -> i, node j >= 2r -> j - r) and run the L steps of
+ * Algorithm 1 on those numbers; at the end each odd node hands the result back to its even
+ * partner.  r = 0 gives Algorithm 1 unchanged. */
+static int sits_out(int r_n, int r) { return r_n < 2 * r && (r_n % 2) == 0; }
+static int folds_in(int r_n, int r) { return r_n < 2 * r && (r_n % 2) == 1; }
+static int step_number(int r_n, int r) { return r_n < 2 * r ? r_n / 2 : r_n - r; }   /* node -> number in the steps */
+static int node_of_number(int v, int r) { return v < r ? 2 * v + 1 : v + r; }
 
 /* ---- chunk partition ------------------------------------------------------------------ */
 
@@ -155,8 +169,8 @@ int nvrar_oracle_allreduce(const void *const *in, void *const *out, int G, int N
                            int dtype, int threads) {
     if (!in || !out || G < 1 || N < 1 || n == 0) return ORACLE_BAD_ARG;
     if (dtype != ORACLE_BF16 && dtype != ORACLE_F32) return ORACLE_BAD_ARG;
-    const int L = log2_exact(N);
-    if (L < 0) return ORACLE_BAD_N;
+    const int L = floor_log2(N);
+    const int r = N - (1 << L);
     const int P = G * N;
     for (int p = 0; p < P; ++p) if (!in[p] || !out[p]) return ORACLE_BAD_ARG;
     if (threads < 1) threads = 1;
@@ -194,13 +208,31 @@ int nvrar_oracle_allreduce(const void *const *in, void *const *out, int G, int N
         leave_ieee(csr);
     }
 
+    /* Phase 2, before the steps (only if N is not a power of two): an odd node among the first
+     * 2r adds what its even partner hands over to its own M'. */
+    #pragma omp parallel for num_threads(threads) schedule(static)
+    for (int p = 0; p < P; ++p) {
+        const int r_n = p / G, r_g = p % G;
+        if (!folds_in(r_n, r)) continue;
+        unsigned csr = enter_ieee();
+        void *own = B_send[0 * P + p];
+        const void *handed = B_send[0 * P + (r_n - 1) * G + r_g];
+        const size_t cnt = chunk_begin(n, G, dtype, r_g + 1) - chunk_begin(n, G, dtype, r_g);
+        for (size_t i = 0; i < cnt; ++i) {
+            float sum = load_elem(handed, i, dtype) + load_elem(own, i, dtype);
+            store_elem(own, i, dtype, sum);
+        }
+        leave_ieee(csr);
+    }
+
     /* Phase 2: inter-node recursive doubling among ranks with equal r_g. */
     for (int l = 0; l < L; ++l) {
         #pragma omp parallel for num_threads(threads) schedule(static)
         for (int p = 0; p < P; ++p) {
-            unsigned csr = enter_ieee();
             const int r_n = p / G, r_g = p % G;
-            const int peer = (r_n ^ (1 << l)) * G + r_g;
+            if (sits_out(r_n, r)) continue;
+            unsigned csr = enter_ieee();
+            const int peer = node_of_number(step_number(r_n, r) ^ (1 << l), r) * G + r_g;
             const void *src = B_send[l * P + p];      /* own data for this step          */
             const void *dst = B_send[l * P + peer];   /* what the peer's put delivers     */
             void *next = B_send[(l + 1) * P + p];
@@ -211,6 +243,15 @@ int nvrar_oracle_allreduce(const void *const *in, void *const *out, int G, int N
             }
             leave_ieee(csr);
         }
+    }
+
+    /* Phase 2, after the steps: the result goes back to the nodes that sat out. */
+    #pragma omp parallel for num_threads(threads) schedule(static)
+    for (int p = 0; p < P; ++p) {
+        const int r_n = p / G, r_g = p % G;
+        if (!sits_out(r_n, r)) continue;
+        const size_t cnt = chunk_begin(n, G, dtype, r_g + 1) - chunk_begin(n, G, dtype, r_g);
+        memcpy(B_send[L * P + p], B_send[L * P + (r_n + 1) * G + r_g], cnt * es);
     }
 
     /* Phase 3: intra-node all-gather.  Rank (r_n, r_g) hands its reduced chunk to every rank

@@ -14,6 +14,9 @@ over node index in natural order.  This file computes exactly that, with whole-a
 float32 operations and no chunking (every element is independent), and narrows to bf16 with
 the integer form of round-to-nearest-even rather than the compare form the C oracle uses.
 The tests require both formulations to agree bit for bit.
+
+For N that is not a power of two (outside the paper) the first 2r nodes, N = 2^L + r, are summed
+pairwise first and the tree runs over the 2^L values that remain, see nvrar_oracle.c.
 """
 from __future__ import annotations
 
@@ -56,8 +59,6 @@ def tree_allreduce(x: np.ndarray, G: int) -> np.ndarray:
     if G < 1 or P % G:
         raise ValueError("G must divide P")
     N = P // G
-    if N & (N - 1):
-        raise ValueError("N must be a power of two")
     dtype = x.dtype
     S0 = []
     for r_n in range(N):
@@ -66,5 +67,16 @@ def tree_allreduce(x: np.ndarray, G: int) -> np.ndarray:
             for g in range(1, G):
                 acc = acc + widen(x[r_n * G + g])
         S0.append(narrow(acc, dtype))
-    total = _tree(S0, 0, N, dtype)
+    # N = 2^L + r: the first 2r nodes are folded pairwise (even into odd) before the tree, and the
+    # tree runs over the 2^L values in the order [folded pairs..., remaining nodes...]
+    L = N.bit_length() - 1
+    r = N - (1 << L)
+    leaves = []
+    for v in range(1 << L):
+        if v < r:
+            with np.errstate(all="ignore"):
+                leaves.append(narrow(widen(S0[2 * v]) + widen(S0[2 * v + 1]), dtype))
+        else:
+            leaves.append(S0[v + r])
+    total = _tree(leaves, 0, 1 << L, dtype)
     return np.broadcast_to(total, (P, n)).copy()

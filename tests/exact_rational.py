@@ -12,7 +12,9 @@ The expression per element is written out from Algorithm 1 / Section 4.1 of the 
   node sum    s(r_n) = bf( f32(..f32(f32(x_0 + x_1) + x_2).. + x_{G-1}) )   local rank order
   step l      v_{l+1}(r_n) = bf( v_l(r_n) + v_l(r_n XOR 2^l) )
   result      v_L(r_n) for every rank of node r_n
-where bf() narrows to the message type (identity for fp32 messages).
+where bf() narrows to the message type (identity for fp32 messages).  For N = 2^L + r that is not
+a power of two the first 2r node sums are first added pairwise, bf(s(2i) + s(2i+1)), and the
+steps run over those r values followed by the remaining nodes' sums.
 """
 from __future__ import annotations
 
@@ -133,16 +135,24 @@ def allreduce_element(vals, G: int, dtype: str):
         for g in range(1, G):
             acc = add_f32_exact(acc, _widen(vals[r_n * G + g], dtype))
         node.append(_narrow(acc, dtype))
-    step = 0
-    while (1 << step) < N:
+    # N = 2^L + r: fold the first 2r nodes pairwise (even node's value arrives at the odd node)
+    L = N.bit_length() - 1
+    r = N - (1 << L)
+    vals = []
+    for v in range(1 << L):
+        if v < r:
+            vals.append(_narrow(add_f32_exact(_widen(node[2 * v], dtype), _widen(node[2 * v + 1], dtype)), dtype))
+        else:
+            vals.append(node[v + r])
+    for step in range(L):
         nxt = []
-        for r_n in range(N):
-            a = _widen(node[r_n], dtype)
-            b = _widen(node[r_n ^ (1 << step)], dtype)
+        for v in range(1 << L):
+            a = _widen(vals[v], dtype)
+            b = _widen(vals[v ^ (1 << step)], dtype)
             nxt.append(_narrow(add_f32_exact(a, b), dtype))
-        node = nxt
-        step += 1
-    return node  # per node; identical entries are asserted by the caller
+        vals = nxt
+    # back to nodes: node 2i and 2i+1 (i < r) share value i, node j >= 2r has value j - r
+    return [vals[q // 2] if q < 2 * r else vals[q - r] for q in range(N)]
 
 
 def allreduce(x: np.ndarray, G: int) -> np.ndarray:

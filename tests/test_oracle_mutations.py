@@ -17,9 +17,22 @@ SRC = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), 
 
 MUTATIONS = {
     "peer distance order reversed":
-        ("const int peer = (r_n ^ (1 << l)) * G + r_g;", "const int peer = (r_n ^ (1 << (L - 1 - l))) * G + r_g;"),
+        ("const int peer = node_of_number(step_number(r_n, r) ^ (1 << l), r) * G + r_g;",
+         "const int peer = node_of_number(step_number(r_n, r) ^ (1 << (L - 1 - l)), r) * G + r_g;"),
     "peer has another local id":
-        ("const int peer = (r_n ^ (1 << l)) * G + r_g;", "const int peer = (r_n ^ (1 << l)) * G + (G - 1 - r_g);"),
+        ("const int peer = node_of_number(step_number(r_n, r) ^ (1 << l), r) * G + r_g;",
+         "const int peer = node_of_number(step_number(r_n, r) ^ (1 << l), r) * G + (G - 1 - r_g);"),
+    "steps pair real node numbers although N is not a power of two":
+        ("const int peer = node_of_number(step_number(r_n, r) ^ (1 << l), r) * G + r_g;",
+         "const int peer = ((r_n ^ (1 << l)) < N ? (r_n ^ (1 << l)) : r_n) * G + r_g;"),
+    "fold pairs (2i+1, 2i+2) instead of (2i, 2i+1)":
+        ("const void *handed = B_send[0 * P + (r_n - 1) * G + r_g];",
+         "const void *handed = B_send[0 * P + ((r_n + 1 < N ? r_n + 1 : r_n - 1)) * G + r_g];"),
+    "the folded-in value is dropped":
+        ("float sum = load_elem(handed, i, dtype) + load_elem(own, i, dtype);", "float sum = load_elem(own, i, dtype);"),
+    "nodes that sat out get a neighbour's input instead of the result":
+        ("memcpy(B_send[L * P + p], B_send[L * P + (r_n + 1) * G + r_g], cnt * es);",
+         "memcpy(B_send[L * P + p], B_send[0 * P + (r_n + 1) * G + r_g], cnt * es);"),
     "narrowing inside the node sum":
         ("for (int g = 1; g < G; ++g) acc = acc + load_elem(in[r_n * G + g], j, dtype);",
          "for (int g = 1; g < G; ++g) { acc = acc + load_elem(in[r_n * G + g], j, dtype);"
@@ -88,7 +101,7 @@ def pins_catch(allreduce) -> bool:
         if any(out[p].tobytes() != w.tobytes() for p in range(x.shape[0])):
             return True
     # exact-rational brute force
-    for P, G in ((4, 2), (8, 2), (8, 4), (16, 4), (16, 1)):
+    for P, G in ((4, 2), (8, 2), (8, 4), (16, 4), (16, 1), (3, 1), (6, 2), (5, 1), (7, 1), (12, 4), (11, 1)):
         for dtype in ("bf16", "f32"):
             x = _adversarial(np.random.default_rng(100 * P + G), P, 48, dtype)
             want, got = ex.allreduce(x, G), allreduce(x, G)
@@ -97,7 +110,7 @@ def pins_catch(allreduce) -> bool:
             if not np.array_equal(got[~nan], want[~nan]):
                 return True
     # closed forms: weighted rank indicator
-    for P, G in ((8, 4), (16, 4), (6, 3)):
+    for P, G in ((8, 4), (16, 4), (6, 3), (6, 2), (20, 4), (7, 1)):
         n = 3 * P + 5
         wind = bf16((np.arange(n)[None, :] % P == np.arange(P)[:, None]) * (np.arange(P)[:, None] + 1.0))
         got = ri.bf16_bits_to_f32(allreduce(wind, G))
