@@ -55,7 +55,7 @@ typedef enum rar_mode {
 typedef enum rar_status {
     RAR_OK = 0,
     RAR_ERR_ARG = -1,     /* NULL pointer, P < 1, G < 1, n == 0, value out of range        */
-    RAR_ERR_SHAPE = -2,   /* G does not divide P, or N = P/G is not a power of two          */
+    RAR_ERR_SHAPE = -2,   /* G does not divide P                                            */
     RAR_ERR_DTYPE = -3,   /* unknown rar_dtype                                              */
     RAR_ERR_LIMIT = -4,   /* P > RAR_MAX_RANKS or n too large for 32-bit vector indices     */
     RAR_ERR_SCRATCH = -5, /* scratch not set, too small, or misaligned                      */
@@ -86,8 +86,12 @@ const char *rar_last_hip_error(void);
  *   ceil(n/G) rounded up to whole 16-byte groups, chunk c covers elements
  *   [min(c*len, n), min((c+1)*len, n)), so trailing chunks may be short or empty (the paper
  *   writes |M|/G and does not treat the ragged case).  N = 1 (no inter-node phase) and G = 1
- *   (phases 1 and 3 reduce to a copy) are valid.  N that is not a power of two is rejected:
- *   the algorithm has no rule for it.
+ *   (phases 1 and 3 reduce to a copy) are valid.  Algorithm 1 assumes N = 2^L.  For any other
+ *   N = 2^L + r the customary extension of recursive doubling is applied (not from the paper):
+ *   nodes (2i, 2i+1), i < r, pair up, the even one hands its reduce-scatter result to the odd
+ *   one and sits out, the 2^L remaining nodes are renumbered (node 2i+1 -> i, node j >= 2r ->
+ *   j - r) and run the L steps on those numbers, and the odd node hands the result back.
+ *   RAR_MODE_FUSED_PACKED is not offered for such N.
  *   *out (host) receives a plan owned by the caller; release it with rar_plan_free.
  *   Touches no device.
  */
@@ -100,8 +104,14 @@ int rar_plan_nodes(const rar_plan_t *plan);
 int rar_plan_steps(const rar_plan_t *plan);
 
 /* Peer of `rank` at inter-node step `step` (0 <= step < L): (r_n XOR 2^step)*G + r_g
- * (Algorithm 1, peer rule of RD_inter).  Negative rar_status on bad arguments. */
+ * (Algorithm 1, peer rule of RD_inter).  If N is not a power of two the XOR acts on the
+ * renumbered nodes, and a rank that sits out the steps gets itself back.  Negative rar_status
+ * on bad arguments. */
 int rar_plan_peer(const rar_plan_t *plan, int rank, int step);
+
+/* The rank that `rank` is paired with before and after the steps when N is not a power of two
+ * (same local id, neighbouring node), or `rank` itself if it has no such partner. */
+int rar_plan_fold_partner(const rar_plan_t *plan, int rank);
 
 /* Element range of chunk c (0 <= c < G): *offset and *length (host, both required). */
 int rar_plan_chunk(const rar_plan_t *plan, int c, size_t *offset, size_t *length);
@@ -119,8 +129,8 @@ size_t rar_plan_scratch_bytes(const rar_plan_t *plan);
 int rar_plan_set_scratch(rar_plan_t *plan, void *scratch, size_t bytes);
 
 /* Execution mode (default RAR_MODE_FUSED).  All modes produce identical bits.
- * RAR_MODE_FUSED_PACKED is accepted only while a chunk is at most 256 KiB (RAR_ERR_LIMIT
- * otherwise); rar_plan_scratch_bytes already includes its buffers for such plans. */
+ * RAR_MODE_FUSED_PACKED is accepted only while a chunk is at most 256 KiB and N is a power of
+ * two (RAR_ERR_LIMIT otherwise); rar_plan_scratch_bytes already includes its buffers for such plans. */
 int rar_plan_set_mode(rar_plan_t *plan, int mode);
 int rar_plan_get_mode(const rar_plan_t *plan);
 

@@ -47,6 +47,7 @@ def _load() -> ctypes.CDLL:
         "rar_plan_nodes": (ci, [vp]),
         "rar_plan_steps": (ci, [vp]),
         "rar_plan_peer": (ci, [vp, ci, ci]),
+        "rar_plan_fold_partner": (ci, [vp, ci]),
         "rar_plan_chunk": (ci, [vp, ci, ctypes.POINTER(sz), ctypes.POINTER(sz)]),
         "rar_plan_scratch_bytes": (sz, [vp]),
         "rar_plan_set_scratch": (ci, [vp, vp, sz]),
@@ -71,7 +72,7 @@ def _load() -> ctypes.CDLL:
 
 lib = _load()
 EXPORTS = ["rar_version", "rar_strerror", "rar_last_hip_error", "rar_plan", "rar_plan_free", "rar_plan_ranks",
-           "rar_plan_nodes", "rar_plan_steps", "rar_plan_peer", "rar_plan_chunk",
+           "rar_plan_nodes", "rar_plan_steps", "rar_plan_peer", "rar_plan_fold_partner", "rar_plan_chunk",
            "rar_plan_scratch_bytes", "rar_plan_set_scratch", "rar_plan_set_mode",
            "rar_plan_get_mode", "rar_plan_set_tuning", "rar_plan_get_tuning",
            "rar_plan_set_wait_limit_us", "rar_plan_status", "rar_step_combine", "rar_allreduce",
@@ -117,6 +118,10 @@ def rar_plan_steps(plan: int) -> int:
 
 def rar_plan_peer(plan: int, rank: int, step: int) -> int:
     return _check(lib.rar_plan_peer(plan, rank, step), "rar_plan_peer")
+
+
+def rar_plan_fold_partner(plan: int, rank: int) -> int:
+    return _check(lib.rar_plan_fold_partner(plan, rank), "rar_plan_fold_partner")
 
 
 def rar_plan_chunk(plan: int, c: int):

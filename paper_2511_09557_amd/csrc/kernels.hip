@@ -135,6 +135,7 @@ struct Shape {
     u64 packed_stride;
     u64 wait_ticks;          // step-barrier time limit in 100 MHz ticks
     u32 P, G, N, L;
+    u32 fold;                // r in N = 2^L + r (0 when N is a power of two)
     u32 chunk_vecs;          // vectors per full chunk
     u32 full_vecs;           // whole vectors in a message
     u32 tail;                // elements in the partial last vector (0 = none)
@@ -339,6 +340,19 @@ __device__ __forceinline__ void wait_for(const Shape &s, const u32 *flag, u32 ex
     __syncthreads();
 }
 
+// N = 2^L + r nodes with r > 0 (outside the paper, whose Algorithm 1 assumes N = 2^L): the
+// customary extension of recursive doubling.  Nodes (2i, 2i+1), i < r, pair up; the even one
+// hands its reduce-scatter result to the odd one and sits out; the 2^L nodes that remain take
+// the numbers (node 2i+1 -> i, node j >= 2r -> j - r) on which the XOR peer rule acts; the odd
+// node finally hands the result back.  With r = 0 every node keeps its own number.
+__device__ __forceinline__ bool sits_out(u32 r_n, u32 fold) { return r_n < 2u * fold && (r_n & 1u) == 0u; }
+__device__ __forceinline__ bool folds_in(u32 r_n, u32 fold) { return r_n < 2u * fold && (r_n & 1u) == 1u; }
+__device__ __forceinline__ u32 peer_node(u32 r_n, u32 l, u32 fold) {
+    const u32 number = r_n < 2u * fold ? r_n >> 1 : r_n - fold;
+    const u32 v = number ^ (1u << l);
+    return v < fold ? 2u * v + 1u : v + fold;
+}
+
 // Workgroup index -> (node, chunk, slot): the N workgroups (one per node) that exchange one
 // (chunk, slot) get consecutive indices.  They are dispatched together, and since workgroups
 // are dealt to the 8 XCDs round-robin by index they sit on different XCDs.  Measured against a
@@ -356,7 +370,9 @@ __device__ __forceinline__ void locate(const Shape &s, u32 block, u32 &r_n, u32 
 // Workgroup (rank p = (r_n, c), slot w) owns slices w, w + B_s, .. of chunk c.  Per slice:
 // reduce-scatter into registers, publish S_0, then for each step wait for the peer's S_l,
 // add it to the partial held in registers, publish S_{l+1} (the last step's result is not
-// exchanged, so it is not written to scratch), finally all-gather from registers.
+// exchanged, so it is not written to scratch), finally all-gather from registers.  If N is not
+// a power of two, a rank that sits out publishes S_0 and all-gathers its partner's S_L, and the
+// partner adds that S_0 to its own before the steps and publishes S_L after them.
 // DATA = false leaves all data movement out (barrier traffic only, for measurement).
 template <int DT, int GT, int U, bool DATA>
 __global__ __launch_bounds__(kThreads) void fused_kernel(RankPtrs bufs, Shape s) {
@@ -373,6 +389,7 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(RankPtrs bufs, Shape s)
     // this slot's counter as the previous call left it (all ranks' slot w hold the same value)
     const u32 base = s.L ? __hip_atomic_load(flag_ptr(s, 0, p, w), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
     bool gave_up = false;
+    const bool idle = sits_out(r_n, s.fold), takes_in = folds_in(r_n, s.fold);
 
     for (u32 it = 0; it < s.iters; ++it) {
         const u32 slice = w + it * s.B_s;
@@ -393,21 +410,36 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(RankPtrs bufs, Shape s)
         uint4 part[U];
         if (DATA) reduce_scatter_slice<DT, GT, U>(bufs, s, r_n, c, v0, valid, whole, part);
         if (s.L) {
+            if (takes_in) {  // the even partner's reduce-scatter result joins before the steps
+                wait_for(s, flag_ptr(s, 0, p - G, w), ticket, gave_up);
+                if (DATA) {
+                    uint4 got[U];
+                    load_slice_coherent<U>(partial_rsrc(s, 0, p - G), s0, v0, valid, whole, got);
+#pragma unroll
+                    for (int u = 0; u < U; ++u) part[u] = combine<DT>(got[u], part[u]);
+                }
+            }
             if (DATA) store_slice_coherent<U>(partial_rsrc(s, 0, p), s0, v0, valid, whole, part);
             publish(flag_ptr(s, 0, p, w), ticket);
         }
-        for (u32 l = 0; l < s.L; ++l) {
-            const u32 peer = (r_n ^ (1u << l)) * G + c;
-            wait_for(s, flag_ptr(s, l, peer, w), ticket, gave_up);
-            if (DATA) {
-                uint4 got[U];
-                load_slice_coherent<U>(partial_rsrc(s, l, peer), s0, v0, valid, whole, got);
+        if (idle) {  // no steps: the odd partner's S_L is the result
+            wait_for(s, flag_ptr(s, s.L, p + G, w), ticket, gave_up);
+            if (DATA) load_slice_coherent<U>(partial_rsrc(s, s.L, p + G), s0, v0, valid, whole, part);
+        } else {
+            for (u32 l = 0; l < s.L; ++l) {
+                const u32 peer = peer_node(r_n, l, s.fold) * G + c;
+                wait_for(s, flag_ptr(s, l, peer, w), ticket, gave_up);
+                if (DATA) {
+                    uint4 got[U];
+                    load_slice_coherent<U>(partial_rsrc(s, l, peer), s0, v0, valid, whole, got);
 #pragma unroll
-                for (int u = 0; u < U; ++u) part[u] = combine<DT>(got[u], part[u]);
-            }
-            if (l + 1 < s.L) {
-                if (DATA) store_slice_coherent<U>(partial_rsrc(s, l + 1, p), s0, v0, valid, whole, part);
-                publish(flag_ptr(s, l + 1, p, w), ticket);
+                    for (int u = 0; u < U; ++u) part[u] = combine<DT>(got[u], part[u]);
+                }
+                // the last step's result is exchanged only if a partner that sat out needs it
+                if (l + 1 < s.L || takes_in) {
+                    if (DATA) store_slice_coherent<U>(partial_rsrc(s, l + 1, p), s0, v0, valid, whole, part);
+                    publish(flag_ptr(s, l + 1, p, w), ticket);
+                }
             }
         }
         if (DATA) all_gather_slice<DT, GT, U>(bufs, s, r_n, c, v0, valid, whole, part);
@@ -570,13 +602,30 @@ __global__ __launch_bounds__(kThreads) void reduce_scatter_kernel(RankPtrs bufs,
     store_slice<U>(partial_buf(a.s, 0, p), v0, valid, whole, part);
 }
 
+// N not a power of two only: S_0(p) = narrow( S_0(p - G) + S_0(p) ) for the ranks of the odd
+// nodes among the first 2r.  In place: a rank's slice of S_0 is read and written by one thread.
+template <int DT, int U>
+__global__ __launch_bounds__(kThreads) void fold_in_kernel(StepShape a) {
+    u32 p, r_n, c, v0, valid;
+    bool whole;
+    step_locate<DT, U>(a, p, r_n, c, v0, valid, whole);
+    if (!folds_in(r_n, a.s.fold)) return;
+    uint4 own[U], got[U];
+    load_slice<U>(partial_buf(a.s, 0, p), v0, valid, whole, own);
+    load_slice<U>(partial_buf(a.s, 0, p - a.s.G), v0, valid, whole, got);
+#pragma unroll
+    for (int u = 0; u < U; ++u) own[u] = combine<DT>(got[u], own[u]);
+    store_slice<U>(partial_buf(a.s, 0, p), v0, valid, whole, own);
+}
+
 // S_{l+1}(p) = narrow( S_l(peer) + S_l(p) )  (Algorithm 1, RD_inter, one step for all ranks)
 template <int DT, int U>
 __global__ __launch_bounds__(kThreads) void exchange_sum_kernel(StepShape a, u32 l) {
     u32 p, r_n, c, v0, valid;
     bool whole;
     step_locate<DT, U>(a, p, r_n, c, v0, valid, whole);
-    const u32 peer = (r_n ^ (1u << l)) * a.s.G + c;
+    if (sits_out(r_n, a.s.fold)) return;
+    const u32 peer = peer_node(r_n, l, a.s.fold) * a.s.G + c;
     uint4 own[U], got[U];
     load_slice<U>(partial_buf(a.s, l, p), v0, valid, whole, own);
     load_slice<U>(partial_buf(a.s, l, peer), v0, valid, whole, got);
@@ -591,7 +640,9 @@ __global__ __launch_bounds__(kThreads) void all_gather_kernel(RankPtrs bufs, Ste
     bool whole;
     step_locate<DT, U>(a, p, r_n, c, v0, valid, whole);
     uint4 part[U];
-    load_slice<U>(partial_buf(a.s, a.s.L, p), v0, valid, whole, part);
+    // a rank that sat out the steps takes the result from its partner on the next node
+    const u32 from = sits_out(r_n, a.s.fold) ? p + a.s.G : p;
+    load_slice<U>(partial_buf(a.s, a.s.L, from), v0, valid, whole, part);
     all_gather_slice<DT, 0, U>(bufs, a.s, r_n, c, v0, valid, whole, part);
 }
 
@@ -636,6 +687,7 @@ static Shape make_shape(const rar_plan_t &plan, const Tuning &t) {
     s.packed_stride = g.packed_stride;
     s.wait_ticks = plan.wait_limit_us * 100ull;  // the wall clock counts at 100 MHz
     s.P = g.P; s.G = g.G; s.N = g.N; s.L = g.L;
+    s.fold = static_cast<u32>(g.fold);
     s.chunk_vecs = static_cast<u32>(g.chunk_vecs);
     s.full_vecs = static_cast<u32>(g.n / g.per_vec);
     s.tail = static_cast<u32>(g.n % g.per_vec);
@@ -786,6 +838,10 @@ static int launch_stepwise_t(const rar_plan_t &plan, const RankPtrs &bufs, hipSt
     const dim3 grid(static_cast<u32>(grid64)), block(kThreads);
     reduce_scatter_kernel<DT, U><<<grid, block, 0, stream>>>(bufs, a);
     if (check_launch() != RAR_OK) return RAR_ERR_HIP;
+    if (g.fold) {
+        fold_in_kernel<DT, U><<<grid, block, 0, stream>>>(a);
+        if (check_launch() != RAR_OK) return RAR_ERR_HIP;
+    }
     for (int l = 0; l < g.L; ++l) {
         exchange_sum_kernel<DT, U><<<grid, block, 0, stream>>>(a, static_cast<u32>(l));
         if (check_launch() != RAR_OK) return RAR_ERR_HIP;

@@ -6,11 +6,10 @@
 
 namespace rar {
 
-static int log2_exact(int v) {
-    if (v < 1) return -1;
+static int floor_log2(int v) {  // largest l with 2^l <= v, v >= 1
     int l = 0;
-    while ((1 << l) < v) ++l;
-    return (1 << l) == v ? l : -1;
+    while ((2 << l) <= v) ++l;
+    return l;
 }
 
 int make_geometry(int P, int G, size_t n, int dtype, Geometry *geo) {
@@ -19,11 +18,11 @@ int make_geometry(int P, int G, size_t n, int dtype, Geometry *geo) {
     if (P > RAR_MAX_RANKS) return RAR_ERR_LIMIT;
     if (P % G != 0) return RAR_ERR_SHAPE;
     const int N = P / G;
-    const int L = log2_exact(N);
-    if (L < 0) return RAR_ERR_SHAPE;
+    const int L = floor_log2(N);
 
     Geometry g;
     g.P = P; g.G = G; g.N = N; g.L = L; g.dtype = dtype; g.n = n;
+    g.fold = N - (1 << L);
     g.elem_bytes = dtype == RAR_BF16 ? 2 : 4;
     g.per_vec = 16 / g.elem_bytes;
     const size_t per_rank = (n + static_cast<size_t>(G) - 1) / static_cast<size_t>(G);
@@ -35,12 +34,13 @@ int make_geometry(int P, int G, size_t n, int dtype, Geometry *geo) {
     // A partial buffer is addressed through a buffer descriptor with 32-bit byte offsets.
     if (g.chunk_stride >= (static_cast<size_t>(1) << 32)) return RAR_ERR_LIMIT;
     g.flags_offset = kHeaderBytes;
-    // One flag per (step buffer l < L, rank, workgroup slot); S_L is never exchanged.
-    g.flags_bytes = round_up(static_cast<size_t>(L > 0 ? L : 1) * P * kMaxWorkgroupsPerRank * 4, kAlign);
+    // One flag per (buffer S_l, rank, workgroup slot).  S_L is exchanged only when N is not a
+    // power of two (it carries the result back to the nodes that sat out).
+    g.flags_bytes = round_up(static_cast<size_t>(L + 1) * P * kMaxWorkgroupsPerRank * 4, kAlign);
     g.data_offset = g.flags_offset + g.flags_bytes;
     g.scratch_bytes = g.data_offset + static_cast<size_t>(L + 1) * P * g.chunk_stride;
     // Data+flag buffers for the packed exchange: one per (step l < L, rank), twice a chunk.
-    if (L > 0 && g.chunk_vecs * 16 <= kPackedMaxChunkBytes) {
+    if (L > 0 && g.fold == 0 && g.chunk_vecs * 16 <= kPackedMaxChunkBytes) {
         g.packed_offset = g.scratch_bytes;
         // whole slices of the largest trip (8 vectors per thread): the word layout inside a
         // slice is strided by thread, so a ragged last slice still spans its full extent
@@ -112,7 +112,7 @@ const char *rar_strerror(int status) {
     switch (status) {
         case RAR_OK: return "ok";
         case RAR_ERR_ARG: return "invalid argument";
-        case RAR_ERR_SHAPE: return "G must divide P and N = P/G must be a power of two";
+        case RAR_ERR_SHAPE: return "G must divide P";
         case RAR_ERR_DTYPE: return "unknown dtype";
         case RAR_ERR_LIMIT: return "size beyond the library's limits";
         case RAR_ERR_SCRATCH: return "scratch not set, too small or misaligned";
@@ -151,7 +151,18 @@ int rar_plan_peer(const rar_plan_t *plan, int rank, int step) {
     const Geometry &g = plan->geo;
     if (rank < 0 || rank >= g.P || step < 0 || step >= g.L) return RAR_ERR_ARG;
     const int r_n = rank / g.G, r_g = rank % g.G;
-    return (r_n ^ (1 << step)) * g.G + r_g;
+    if (rar::sits_out(r_n, g.fold)) return rank;
+    return rar::node_of_number(rar::step_number(r_n, g.fold) ^ (1 << step), g.fold) * g.G + r_g;
+}
+
+int rar_plan_fold_partner(const rar_plan_t *plan, int rank) {
+    if (!plan) return RAR_ERR_ARG;
+    const Geometry &g = plan->geo;
+    if (rank < 0 || rank >= g.P) return RAR_ERR_ARG;
+    const int r_n = rank / g.G;
+    if (rar::sits_out(r_n, g.fold)) return rank + g.G;
+    if (rar::folds_in(r_n, g.fold)) return rank - g.G;
+    return rank;
 }
 
 int rar_plan_chunk(const rar_plan_t *plan, int c, size_t *offset, size_t *length) {

@@ -22,6 +22,7 @@ inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct Geometry {
     int P = 0, G = 0, N = 0, L = 0;
+    int fold = 0;            // r in N = 2^L + r: the first 2r nodes are folded pairwise (0 = N is a power of two)
     int dtype = RAR_BF16;
     size_t n = 0;            // elements per rank
     size_t elem_bytes = 0;   // 2 or 4
@@ -58,6 +59,16 @@ namespace rar {
 
 // Fill geo from (P, G, n, dtype); returns a rar_status.
 int make_geometry(int P, int G, size_t n, int dtype, Geometry *geo);
+
+// N = 2^L + r that is not a power of two (outside the paper, whose Algorithm 1 assumes 2^L
+// nodes): the customary extension of recursive doubling.  Nodes (2i, 2i+1), i < r, pair up; the
+// even one hands its reduce-scatter result to the odd one and sits out; the 2^L nodes that
+// remain are renumbered (node 2i+1 -> i, node j >= 2r -> j - r) and run the L steps on those
+// numbers; the odd node finally hands the result back to its even partner.
+inline bool sits_out(int r_n, int fold) { return r_n < 2 * fold && (r_n % 2) == 0; }
+inline bool folds_in(int r_n, int fold) { return r_n < 2 * fold && (r_n % 2) == 1; }
+inline int step_number(int r_n, int fold) { return r_n < 2 * fold ? r_n / 2 : r_n - fold; }
+inline int node_of_number(int v, int fold) { return v < fold ? 2 * v + 1 : v + fold; }
 
 inline size_t chunk_begin(const Geometry &g, int c) {
     size_t b = static_cast<size_t>(c) * g.chunk_len;

@@ -30,15 +30,27 @@ static void check_shape(int P, int G, size_t n, int dtype) {
     }
     CHECK(pos == n);
     CHECK(g.chunk_stride >= g.chunk_vecs * 16 && g.chunk_stride % 256 == 0);
-    CHECK(g.flags_bytes >= static_cast<size_t>(g.L) * P * rar::kMaxWorkgroupsPerRank * 4);
+    CHECK(g.flags_bytes >= static_cast<size_t>(g.L + 1) * P * rar::kMaxWorkgroupsPerRank * 4);
+    CHECK(g.N == (1 << g.L) + g.fold && g.fold >= 0 && g.fold < (1 << g.L));
+    CHECK(g.fold == 0 || g.packed_offset == 0);
     CHECK(g.data_offset % 256 == 0);
     CHECK(g.scratch_bytes >= g.data_offset + static_cast<size_t>(g.L + 1) * P * g.chunk_stride);
-    // peers: mutual, same local id, all nodes reached
-    for (int p = 0; p < P; ++p)
+    // peers: mutual, same local id; a node that sits out has a partner on the next node that
+    // takes part, and nothing reaches past rank P - 1
+    for (int p = 0; p < P; ++p) {
+        const int partner = rar_plan_fold_partner(plan, p);
+        CHECK(partner >= 0 && partner < P && partner % G == p % G);
+        CHECK(rar_plan_fold_partner(plan, partner) == p);
+        const bool idle = rar::sits_out(p / G, g.fold);
+        CHECK(!idle || partner == p + G);
+        CHECK(!rar::folds_in(p / G, g.fold) || partner == p - G);
         for (int l = 0; l < g.L; ++l) {
             const int q = rar_plan_peer(plan, p, l);
+            if (idle) { CHECK(q == p); continue; }
             CHECK(q >= 0 && q < P && q % G == p % G && rar_plan_peer(plan, q, l) == p && q != p);
+            CHECK(!rar::sits_out(q / G, g.fold));
         }
+    }
     // every tuning the launchers can see keeps all accesses inside the buffers
     const long resident_cases[3][4] = {{0, 0, 0, 0}, {2048, 2048, 1024, 512}, {256, 256, 256, 256}};
     const size_t C_values[5] = {0, 4096, 8192, 16384, 32768};
@@ -96,11 +108,11 @@ int main() {
     const int Gs[] = {1, 2, 3, 4, 5, 8};
     const size_t ns[] = {1, 7, 8, 9, 63, 64, 65, 1000, 4096, 65536, 65537, 1048576, 33554432, 100000007};
     for (int G : Gs)
-        for (int N = 1; N * G <= RAR_MAX_RANKS; N *= 2)
+        for (int N = 1; N * G <= RAR_MAX_RANKS; N = N < 8 ? N + 1 : N < 16 ? N + 3 : N * 2 - 5)
             for (size_t n : ns)
                 for (int dtype = 0; dtype < 2; ++dtype) check_shape(N * G, G, n, dtype);
     for (int G : Gs)
-        for (int N = 1; N <= 8 && N * G <= 32; N *= 2)
+        for (int N = 1; N <= 9 && N * G <= 36; ++N)
             for (size_t n : {size_t(1), size_t(7), size_t(33), size_t(1001)})
                 for (int dtype = 0; dtype < 2; ++dtype) check_oracle(N * G, G, n, dtype);
     std::printf(failures ? "host checks FAILED: %d\n" : "host checks ok\n", failures);

@@ -35,7 +35,8 @@ def test_native_program_builds(tmp_path):
 
 
 @pytest.mark.gpu
-@pytest.mark.parametrize("P,G,n,dtype", [(8, 4, 65536, 0), (16, 4, 100003, 1), (64, 4, 1048576, 0), (12, 3, 4099, 0)])
+@pytest.mark.parametrize("P,G,n,dtype", [(8, 4, 65536, 0), (16, 4, 100003, 1), (64, 4, 1048576, 0), (12, 3, 4099, 0),
+                                          (12, 4, 4099, 0), (40, 8, 100003, 1)])
 def test_native_program_matches_oracle(tmp_path, P, G, n, dtype):
     exe = build_native(tmp_path)
     print(f"[gpu] native C program P={P} G={G} n={n} dtype={dtype}", flush=True)

@@ -209,7 +209,10 @@ def test_sweep_large_points_sampled(P, G, nbytes, dtype):
 
 EDGE = [(1, 1, 1), (1, 1, 1000), (2, 1, 9), (2, 2, 9), (4, 4, 3), (4, 2, 17), (8, 4, 1), (8, 4, 7),
         (8, 4, 31), (8, 4, 33), (8, 4, 4 * 8 * 256 + 5), (8, 8, 1029), (16, 1, 4097), (16, 4, 65536 + 24),
-        (32, 8, 12345), (128, 4, 1001), (128, 8, 40000), (6, 3, 1000), (12, 3, 77), (5, 5, 64)]
+        (32, 8, 12345), (128, 4, 1001), (128, 8, 40000), (6, 3, 1000), (12, 3, 77), (5, 5, 64),
+        # N that is not a power of two (outside the paper): N = 3, 5, 6, 7, 9, 11, 25, 31
+        (12, 4, 1000), (3, 1, 9), (20, 4, 65536 + 24), (18, 3, 4099), (7, 1, 513), (36, 4, 262144),
+        (88, 8, 30000), (100, 4, 50001), (124, 4, 8 * 4096)]
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
@@ -219,6 +222,12 @@ def test_edge_shapes(P, G, n, dtype):
     want = oracle.allreduce(x, G)
     assert_same_bits(run_gpu(x, G, "fused"), want, "fused")
     assert_same_bits(run_gpu(x, G, "stepwise"), want, "stepwise")
+    N = P // G
+    if N & (N - 1):
+        # the data+flag mode is offered for N = 2^L only; several trips per workgroup instead
+        # (three or more make a workgroup reuse its two places in every partial buffer)
+        assert_same_bits(run_gpu(x, G, "fused", B_s=1, C_s=4096, calls=1), want, "fused, one workgroup per rank")
+        return
     assert_same_bits(run_gpu(x, G, "packed"), want, "packed")
     assert_same_bits(run_gpu(x, G, "packed", B_s=1, C_s=4096), want, "packed, one workgroup per rank")
 
@@ -286,6 +295,36 @@ def test_repeated_calls_in_place():
     assert_same_bits(run_gpu(x, w.G, "stepwise", calls=3), want, "stepwise x3")
     assert_same_bits(run_gpu(x, w.G, "packed", calls=3), want, "packed x3")
     assert_same_bits(run_gpu(x, w.G, "packed", B_s=2, C_s=4096, calls=3), want, "packed x3, several trips")
+
+
+def test_odd_node_count_under_replay():
+    """N = 6 nodes (outside the paper): 300 fused calls with fresh inputs and changing launch shapes
+    against the stepwise path; the hand-over before and after the steps uses the same flags."""
+    P, G, n = 24, 4, 96 * 1024
+    a = rar.AllReduce(P, G, n, 0, 1)
+    b = rar.AllReduce(P, G, n, 0, 0)
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(4321)
+    src = torch.empty(P, n, device="cuda:0", dtype=torch.bfloat16)
+    wa, wb = torch.empty_like(src), torch.empty_like(src)
+    a.bind([wa[p] for p in range(P)])
+    b.bind([wb[p] for p in range(P)])
+    print("[gpu] replay stress, N = 6", flush=True)
+    shapes = [(0, 0), (2, 4096), (3, 4096), (1, 8192), (5, 16384), (1, 32768)]
+    for it in range(300):
+        if it % 10 == 0:
+            src.copy_(torch.randn(P, n, device="cuda:0", generator=gen))
+        else:
+            src.mul_(0.5)
+        wa.copy_(src), wb.copy_(src)
+        a.set_tuning(*shapes[(it // 3) % len(shapes)])
+        a.launch(), b.launch()
+        assert torch.equal(wa.view(torch.int16), wb.view(torch.int16)), ("fused", it)
+        assert torch.equal(wb[P - 1].view(torch.int16), wb[0].view(torch.int16)), ("ranks differ", it)
+    assert a.status() == 0
+    x = src.cpu().view(torch.int16).numpy().view(np.uint16)
+    assert_same_bits(wb.cpu().view(torch.int16).numpy().view(np.uint16), oracle.allreduce(x, G, threads=8), "stepwise, last input")
+    a.close(), b.close()
 
 
 def test_fused_equals_stepwise_under_replay():

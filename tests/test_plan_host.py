@@ -28,8 +28,7 @@ def test_version_and_strerror():
     assert rar.rar_strerror(-99) == "unknown status"
 
 
-@pytest.mark.parametrize("P,G,status", [(0, 1, -1), (8, 0, -1), (12, 4, -2), (10, 4, -2), (24, 8, -2),
-                                        (256, 4, -4), (8, 16, -2)])
+@pytest.mark.parametrize("P,G,status", [(0, 1, -1), (8, 0, -1), (10, 4, -2), (20, 8, -2), (256, 4, -4), (8, 16, -2)])
 def test_plan_rejects(P, G, status):
     with pytest.raises(rar.RarError) as e:
         rar.rar_plan(P, G, 1024, 0)
@@ -71,6 +70,53 @@ def test_peer_rule_exhaustive():
                     rar.rar_plan_peer(plan, p, L)
             with pytest.raises(rar.RarError):
                 rar.rar_plan_peer(plan, P, 0)
+            rar.rar_plan_free(plan)
+
+
+def test_peer_rule_any_node_count():
+    """N = 2^L + r (outside the paper): r even nodes hand over and sit out, the rest run the XOR
+    rule on their renumbering, and every node's contribution reaches every node that takes part."""
+    for G in (1, 3, 4):
+        for N in range(1, 33):
+            P = G * N
+            if P > 128:
+                continue
+            plan = rar.rar_plan(P, G, 4096, 0)
+            L = rar.rar_plan_steps(plan)
+            r = N - (1 << L)
+            assert 0 <= r < (1 << L) and rar.rar_plan_nodes(plan) == N
+            idle = {m for m in range(2 * r) if m % 2 == 0}
+            for g in range(G):
+                holds = {m: {m} for m in range(N)}        # node -> nodes whose data it has summed
+                for m in range(N):
+                    q = rar.rar_plan_fold_partner(plan, m * G + g)
+                    assert q % G == g and rar.rar_plan_fold_partner(plan, q) == m * G + g
+                    if m in idle:
+                        assert q == (m + 1) * G + g
+                        holds[m + 1] = holds[m + 1] | {m}
+                    elif m < 2 * r:
+                        assert q == (m - 1) * G + g
+                    else:
+                        assert q == m * G + g
+                for l in range(L):
+                    nxt = dict(holds)
+                    for m in range(N):
+                        q = rar.rar_plan_peer(plan, m * G + g, l)
+                        if m in idle:
+                            assert q == m * G + g
+                            continue
+                        assert q % G == g and q // G not in idle and q // G != m
+                        assert rar.rar_plan_peer(plan, q, l) == m * G + g
+                        assert not (holds[m] & holds[q // G])   # nothing is counted twice
+                        nxt[m] = holds[m] | holds[q // G]
+                    holds = nxt
+                for m in range(N):
+                    if m not in idle:
+                        assert holds[m] == set(range(N))
+            if r:
+                with pytest.raises(rar.RarError) as e:     # the data+flag mode is for N = 2^L only
+                    rar.rar_plan_set_mode(plan, 2)
+                assert e.value.status == -4
             rar.rar_plan_free(plan)
 
 
