@@ -29,6 +29,10 @@ int ensure_flags(rar_plan_t *plan, hipStream_t stream) {
 
 int ensure_residency(rar_plan_t *plan) {
     if (plan->have_resident) return RAR_OK;
+    rar::DeviceInfo info;
+    int got = rar::device_info(&info);
+    if (got != RAR_OK) return got;
+    plan->compute_units = info.compute_units;
     for (int i = 0; i < 4; ++i) {
         int rc = rar::fused_max_resident(plan->geo.dtype, plan->geo.G, 1 << i, false, &plan->resident[i]);
         if (rc != RAR_OK) return rc;

@@ -68,20 +68,34 @@ Tuning resolve_tuning(const rar_plan_t &plan, const long *max_resident) {
                                  (static_cast<size_t>(kThreads) * unroll));
     };
 
+    // Built-in choice, from a scan of all (B_s, C_s) on MI355X over P = 8..128, G = 1..8, 16 KiB to
+    // 16 MiB, both types.  Four workgroups per compute unit keep the memory system busy, and
+    // more of them only add step barriers (two per compute unit already do with four or more
+    // steps, where barriers weigh more).  So: the smallest trip whose slices fit in that many
+    // workgroups, one slice each.  A message too long for that runs 16 KiB trips on four
+    // workgroups per compute unit (32 KiB trips when a rank reads at most two buffers per
+    // element, so that a thread still has 16 loads in flight; half the workgroups when it
+    // reads eight or more).
+    const long target = 4L * (plan.compute_units > 0 ? plan.compute_units : 256);
+    const long small_target = g.L >= 4 ? target / 2 : target;
+    long grid_cap = kMaxWorkgroupsPerRank;  // workgroups per rank beyond which the built-in choice does not go
     Tuning t{};
     int index = 3;
     if (plan.user_C_s) {
         t.unroll = static_cast<int>(plan.user_C_s / (static_cast<size_t>(kThreads) * 16));
         index = t.unroll == 1 ? 0 : t.unroll == 2 ? 1 : t.unroll == 4 ? 2 : 3;
     } else {
-        // 16 KiB trips (4 vectors per thread) amortise the step barriers best on MI355X; take
-        // smaller trips only while the grid would leave most of the 256 compute units idle.
-        index = 2;
-        auto grid = [&](int i) {
-            const long per_rank = slices(1 << i) < cap_for(i) ? slices(1 << i) : cap_for(i);
-            return per_rank * g.P;
-        };
-        while (index > 0 && grid(index) < 256) --index;
+        index = 0;
+        while (index < 2 && slices(1 << index) * g.P > small_target) ++index;
+        if (slices(1 << index) * g.P > small_target) {
+            if (g.G > 2 && slices(4) * g.P <= target) {
+                index = 2;
+            } else {  // the long-message regime
+                index = g.G <= 2 ? 3 : 2;
+                grid_cap = (g.G >= 8 ? target / 2 : target) / g.P;
+                if (grid_cap < 1) grid_cap = 1;
+            }
+        }
         t.unroll = 1 << index;
     }
     const long cap = cap_for(index);
@@ -92,6 +106,7 @@ Tuning resolve_tuning(const rar_plan_t &plan, const long *max_resident) {
         if (want > all) want = all;
     } else {
         want = all < cap ? all : cap;  // one slice per workgroup if the device can hold them all
+        if (want > grid_cap) want = grid_cap;
     }
     if (want < 1) want = 1;
     t.B_s = static_cast<int>(want);

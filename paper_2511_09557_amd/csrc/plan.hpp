@@ -53,6 +53,7 @@ struct rar_plan_s {
     long resident[4] = {0, 0, 0, 0};  // cached residency of the fused kernel per unroll 1,2,4,8
     long resident_packed[4] = {0, 0, 0, 0};  // same for the packed fused kernel
     bool have_resident = false;
+    int compute_units = 256;   // of the device the residency was measured on (MI355X until then)
 };
 
 namespace rar {
