@@ -95,6 +95,24 @@ def copy_probe(times: int = 3) -> None:
     torch.cuda.synchronize()
 
 
+def bench_step_combine(warmup: int, steps: int):
+    """rar_step_combine (one rank's exchange-and-sum, 3 * n * 2 bytes of traffic) on c4's per-step
+    message (512 KiB, launch-bound) and on 128 MiB (bandwidth-bound; beyond the memory-side cache)."""
+    import torch
+    import paper_2511_09557_amd as rar
+    out = {}
+    st = torch.cuda.current_stream().cuda_stream
+    for label, n in (("512KiB", 262144), ("128MiB", 64 << 20)):
+        dst = torch.zeros(n, dtype=torch.bfloat16, device="cuda:0")
+        src = torch.ones(n, dtype=torch.bfloat16, device="cuda:0")
+        k = max(steps // 10, 10) if n > (1 << 22) else steps
+        _, ev = time_calls(lambda: rar.rar_step_combine(dst.data_ptr(), src.data_ptr(), 0, n, rar.RAR_BF16, st), min(warmup, 20), k)
+        us = ev * 1000.0 / k
+        out[label] = {"elements": n, "us": us, "GBps": 3 * n * 2 / (us * 1e-6) / 1e9}
+        del dst, src
+    return out
+
+
 def measured_traffic(workload: str):
     """HBM bytes per fused launch from the committed rocprofv3 --pmc summary (None if absent or
     for another workload).  bench.py cannot collect hardware counters itself."""
@@ -319,6 +337,25 @@ def hierarchy(path: str) -> None:
             G *= 2
         lines.append("")
         print(f"P={P} {nbytes} B done", file=sys.stderr, flush=True)
+    # node counts that are not powers of two (outside the paper): N = 2^L + r costs the L steps
+    # plus a hand-over before and after them on the first 2r nodes
+    lines += ["## G = 4, any N (N that is not a power of two is an extension outside the paper)", "",
+              "| N | P | L | folded pairs r | us per all-reduce, 256 KiB | us per all-reduce, 2048 KiB |", "|---|---|---|---|---|---|"]
+    for N in range(2, 17):
+        P, row = 4 * N, []
+        for nbytes in (256 << 10, 2 << 20):
+            n = nbytes // 2
+            whole = torch.randn(P, n, device="cuda:0", generator=gen).to(torch.bfloat16)
+            bufs = [whole[p] for p in range(P)]
+            ar = rar.AllReduce(P, 4, n, rar.RAR_BF16, rar.RAR_MODE_FUSED)
+            ar.bind(bufs)
+            row.append(time_graph(lambda st: ar.launch(st), 100, 2, 10))
+            assert ar.status() == 0
+            ar.close()
+            del bufs, whole
+        L = N.bit_length() - 1
+        lines.append(f"| {N} | {P} | {L} | {N - (1 << L)} | {row[0]:.2f} | {row[1]:.2f} |")
+    lines.append("")
     with open(path, "w") as f:
         f.write("\n".join(lines) + "\n")
 
@@ -341,8 +378,16 @@ def cpu_baseline(name: str):
         if time.perf_counter() - t0 > 10.0 or reps >= 50:
             break
     per = (time.perf_counter() - t0) / reps
+    t1 = time.perf_counter()
+    single_reps = 0
+    while single_reps < 3 and (single_reps == 0 or time.perf_counter() - t1 < 5.0):
+        oracle.allreduce(x, w.G, threads=1)
+        single_reps += 1
+    single = (time.perf_counter() - t1) / single_reps
     return {"value": per * 1e6, "unit": "us per all-reduce", "cores": cores, "kind": "oracle",
-            "sample": f"{reps} whole all-reduces of workload {name} (P={w.P}, {w.bytes_per_rank} B per rank)"}
+            "sample": f"{reps} whole all-reduces of workload {name} (P={w.P}, {w.bytes_per_rank} B per rank)",
+            "single_thread": {"value": single * 1e6, "unit": "us per all-reduce", "cores": 1,
+                              "sample": f"{single_reps} whole all-reduces of the same workload"}}
 
 
 def main() -> int:
@@ -383,7 +428,7 @@ def main() -> int:
     achieved = head["algorithmic_bytes"] / (us * 1e-6) / 1e9
     traffic = measured_traffic(args.workload)
     line = {
-        "metric": "us per all-reduce (fused schedule, bf16, P virtual ranks on one GPU); achieved HBM GB/s vs peak",
+        "metric": "us per all-reduce at 128KB-2MB bf16 (P virtual ranks); achieved HBM GB/s vs peak",
         "value": us,
         "unit": "us",
         "n_gpus": 1,
@@ -416,6 +461,7 @@ def main() -> int:
         for k, v in detail.items():
             v["achieved_GBps"] = v["algorithmic_bytes"] / (v["fused_us"] * 1e-6) / 1e9
         line["detail"] = detail
+        line["step_combine"] = bench_step_combine(args.warmup, args.steps)
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline(args.workload)
     print(json.dumps(line))
