@@ -136,22 +136,23 @@ def bench_workload(name: str, warmup: int, steps: int, extras: bool):
     bufs = device_bufs(x)
     ar = rar.AllReduce(w.P, w.G, w.n, dtype, rar.RAR_MODE_FUSED)
     ar.bind(bufs)
-    wall, ev_ms = time_calls(lambda: ar.launch(), warmup, steps)
+    cur = torch.cuda.current_stream().cuda_stream   # looked up once: the timed calls pass the handle
+    wall, ev_ms = time_calls(lambda: ar.launch(cur), warmup, steps)
     assert ar.status() == 0
     out["fused_us"] = ev_ms * 1000.0 / steps
     out["fused_wall_us"] = wall * 1e6 / steps
     if extras:  # two more repetitions of the same timed region, to show the spread
-        reps = [out["fused_us"]] + [time_calls(lambda: ar.launch(), 10, steps)[1] * 1000.0 / steps for _ in range(2)]
+        reps = [out["fused_us"]] + [time_calls(lambda: ar.launch(cur), 10, steps)[1] * 1000.0 / steps for _ in range(2)]
         out["fused_us_repetitions"] = reps
     out["tuning"] = dict(zip(("B_s", "C_s"), ar.tuning()))
     if extras:
         ar.set_mode(rar.RAR_MODE_STEPWISE)
-        _, ev = time_calls(lambda: ar.launch(), warmup // 4 + 1, max(steps // 4, 10))
+        _, ev = time_calls(lambda: ar.launch(cur), warmup // 4 + 1, max(steps // 4, 10))
         out["stepwise_us"] = ev * 1000.0 / max(steps // 4, 10)
         ar.set_mode(rar.RAR_MODE_FUSED)
-        _, ev = time_calls(lambda: ar.launch_floor(), warmup, steps)
+        _, ev = time_calls(lambda: ar.launch_floor(cur), warmup, steps)
         out["launch_floor_us"] = ev * 1000.0 / steps
-        _, ev = time_calls(lambda: ar.barrier_only(), warmup, steps)
+        _, ev = time_calls(lambda: ar.barrier_only(cur), warmup, steps)
         out["barrier_only_us"] = ev * 1000.0 / steps
         # the same three things inside HIP graphs of 100 calls: the device-side cost without
         # the host's launch rate.  floor = launch only; barrier = flags only; fused = everything
@@ -185,7 +186,7 @@ def bench_workload(name: str, warmup: int, steps: int, extras: bool):
         except rar.RarError:
             out["packed_us"] = out["graph100_packed_us"] = None
         else:
-            _, ev = time_calls(lambda: ar.launch(), warmup, steps)
+            _, ev = time_calls(lambda: ar.launch(cur), warmup, steps)
             out["packed_us"] = ev * 1000.0 / steps
             out["graph100_packed_us"] = time_graph(lambda st: ar.launch(st), 100, 2, 10)
             out["packed_tuning"] = dict(zip(("B_s", "C_s"), ar.tuning()))

@@ -220,10 +220,12 @@ class AllReduce:
         self._bound_ptrs = None
 
     def _stream(self, stream) -> int:
-        import torch
+        if isinstance(stream, int):      # a raw hipStream_t handle: nothing to look up
+            return stream
         if stream is None:
+            import torch
             return torch.cuda.current_stream().cuda_stream
-        return stream if isinstance(stream, int) else stream.cuda_stream
+        return stream.cuda_stream
 
     def bind(self, tensors) -> None:
         """Check P tensors (one per virtual rank, n elements each) and keep their addresses, so

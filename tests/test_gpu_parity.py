@@ -212,7 +212,9 @@ EDGE = [(1, 1, 1), (1, 1, 1000), (2, 1, 9), (2, 2, 9), (4, 4, 3), (4, 2, 17), (8
         (32, 8, 12345), (128, 4, 1001), (128, 8, 40000), (6, 3, 1000), (12, 3, 77), (5, 5, 64),
         # N that is not a power of two (outside the paper): N = 3, 5, 6, 7, 9, 11, 25, 31
         (12, 4, 1000), (3, 1, 9), (20, 4, 65536 + 24), (18, 3, 4099), (7, 1, 513), (36, 4, 262144),
-        (88, 8, 30000), (100, 4, 50001), (124, 4, 8 * 4096)]
+        (88, 8, 30000), (100, 4, 50001), (124, 4, 8 * 4096),
+        # the most steps the library allows: N = 128 (L = 7), and N = 96, 127 (L = 6, r = 32, 63)
+        (128, 1, 5000), (64, 1, 60000), (128, 2, 70001), (96, 1, 777), (127, 1, 30000)]
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
