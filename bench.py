@@ -18,7 +18,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
 COPY_PROBE_BYTES = 256 << 20  # the known-size copy that rocprof's byte counters are scaled by
 SWEEP_SEED = 20251109 * 1000 + 400
-TRAFFIC_FILE = os.path.join(ROOT, "profiles", "fused_kernel_c4_traffic.json")
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "fused_kernel_{workload}_traffic.json")
 
 
 def algorithmic_bytes(P: int, G: int, N: int, msg_bytes: int) -> int:
@@ -117,7 +117,7 @@ def measured_traffic(workload: str):
     """HBM bytes per fused launch from the committed rocprofv3 --pmc summary (None if absent or
     for another workload).  bench.py cannot collect hardware counters itself."""
     try:
-        with open(TRAFFIC_FILE) as f:
+        with open(TRAFFIC_FILE.format(workload=workload)) as f:
             t = json.load(f)
         return t["bytes_per_launch"] if t.get("workload") == workload else None
     except (OSError, ValueError, KeyError):
@@ -461,6 +461,7 @@ def main() -> int:
                 detail[other] = bench_workload(other, args.warmup, max(args.steps // 2, 10), extras=True)
         for k, v in detail.items():
             v["achieved_GBps"] = v["algorithmic_bytes"] / (v["fused_us"] * 1e-6) / 1e9
+            v["traffic"] = measured_traffic(k)   # HBM bytes per launch from the committed --pmc summaries
         line["detail"] = detail
         line["step_combine"] = bench_step_combine(args.warmup, args.steps)
     if not args.no_cpu:
