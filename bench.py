@@ -191,6 +191,13 @@ def bench_workload(name: str, warmup: int, steps: int, extras: bool):
             out["graph100_packed_us"] = time_graph(lambda st: ar.launch(st), 100, 2, 10)
             out["packed_tuning"] = dict(zip(("B_s", "C_s"), ar.tuning()))
             ar.set_mode(rar.RAR_MODE_FUSED)
+        # what a caller who sets nothing gets (the library's automatic choice between the two)
+        ar.set_mode(rar.RAR_MODE_AUTO)
+        packed = ar.effective_mode() == rar.RAR_MODE_FUSED_PACKED
+        out["auto_mode"] = "fused_packed" if packed else "fused"
+        out["auto_us"] = out["packed_us"] if packed else out["fused_us"]
+        out["graph100_auto_us"] = out["graph100_packed_us"] if packed else out["graph100_us"]
+        ar.set_mode(rar.RAR_MODE_FUSED)
         assert ar.status() == 0
     ar.close()
     return out
@@ -222,6 +229,15 @@ def sweep(path: str) -> None:
                     _, ev = time_calls(lambda: ar.launch(), max(reps // 5, 2), reps)
                     fused = ev * 1000.0 / reps
                     graph = time_graph(lambda st: ar.launch(st), 20, 1, max(reps // 20, 2)) if nbytes <= (4 << 20) else None
+                    packed_graph = None
+                    if nbytes <= (1 << 20):
+                        try:
+                            ar.set_mode(rar.RAR_MODE_FUSED_PACKED)
+                            packed_graph = time_graph(lambda st: ar.launch(st), 20, 1, max(reps // 20, 2))
+                        except rar.RarError:
+                            pass
+                    ar.set_mode(rar.RAR_MODE_AUTO)
+                    auto = "packed" if ar.effective_mode() == rar.RAR_MODE_FUSED_PACKED else "fused"
                     ar.set_mode(rar.RAR_MODE_STEPWISE)
                     _, ev = time_calls(lambda: ar.launch(), max(reps // 5, 2), reps)
                     stepwise = ev * 1000.0 / reps
@@ -229,7 +245,8 @@ def sweep(path: str) -> None:
                     B_s, C_s = ar.tuning()
                     ar.close()
                     row = {"dtype": dtype, "P": P, "G": G, "bytes_per_rank": nbytes, "fused_us": fused,
-                           "fused_in_graph_us": graph, "stepwise_us": stepwise, "algorithmic_bytes": alg,
+                           "fused_in_graph_us": graph, "packed_in_graph_us": packed_graph, "auto_mode": auto,
+                           "stepwise_us": stepwise, "algorithmic_bytes": alg,
                            "fused_GBps": alg / (fused * 1e-6) / 1e9, "B_s": B_s, "C_s": C_s}
                     f.write(json.dumps(row) + "\n")
                     f.flush()
@@ -243,18 +260,20 @@ def sweep(path: str) -> None:
     with open(md, "w") as f:
         f.write("# Message-size sweep of the all-reduce on one MI355X\n\n"
                 "command: `python3 bench.py --sweep <file>.jsonl`; eager launches timed with HIP events; values N(0,1)\n"
-                "drawn on the device; GB/s = algorithmic bytes `P*(2M + (3L+2)M/G)` / time; `graph` = the fused call\n"
-                "inside a HIP graph of 20 calls (messages up to 4 MiB), which takes the host's launch rate out.\n")
+                "drawn on the device; GB/s = algorithmic bytes `P*(2M + (3L+2)M/G)` / time; `graph` = the call inside a\n"
+                "HIP graph of 20 calls (fused: messages up to 4 MiB; data+flag mode: up to 1 MiB), which takes the host's\n"
+                "launch rate out; `auto` = the mode a plan runs in when none is set.\n")
         key = None
         for r in rows:
             if (r["dtype"], r["P"], r["G"]) != key:
                 key = (r["dtype"], r["P"], r["G"])
                 f.write(f"\n## {r['dtype']}, P={r['P']} (G={r['G']}, N={r['P'] // r['G']})\n\n"
-                        "| bytes per rank | fused us | fused GB/s | frac of 8 TB/s | fused in graph us | stepwise us | B_s | C_s |\n"
-                        "|---|---|---|---|---|---|---|---|\n")
+                        "| bytes per rank | fused us | fused GB/s | frac of 8 TB/s | fused in graph us | data+flag in graph us | auto | stepwise us | B_s | C_s |\n"
+                        "|---|---|---|---|---|---|---|---|---|---|\n")
             g = "-" if r["fused_in_graph_us"] is None else f"{r['fused_in_graph_us']:.2f}"
+            pg = "-" if r["packed_in_graph_us"] is None else f"{r['packed_in_graph_us']:.2f}"
             f.write(f"| {r['bytes_per_rank']} | {r['fused_us']:.2f} | {r['fused_GBps']:.0f} | {r['fused_GBps'] / HBM_PEAK_GBPS:.3f} "
-                    f"| {g} | {r['stepwise_us']:.2f} | {r['B_s']} | {r['C_s']} |\n")
+                    f"| {g} | {pg} | {r['auto_mode']} | {r['stepwise_us']:.2f} | {r['B_s']} | {r['C_s']} |\n")
 
 
 def sensitivity(path: str) -> None:

@@ -45,11 +45,14 @@ typedef enum rar_dtype {
 
 typedef enum rar_mode {
     RAR_MODE_STEPWISE = 0, /* one launch per phase: 1 reduce-scatter + L steps + 1 all-gather */
-    RAR_MODE_FUSED = 1,    /* one persistent launch; flag-based step barriers (default)      */
-    RAR_MODE_FUSED_PACKED = 2 /* one persistent launch; every 8-byte word exchanged carries 4 bytes of
+    RAR_MODE_FUSED = 1,    /* one persistent launch; flag-based step barriers                */
+    RAR_MODE_FUSED_PACKED = 2, /* one persistent launch; every 8-byte word exchanged carries 4 bytes of
                               data and the call's 4-byte sequence number (Section 4.2.2, the
                               low-latency payload), so a step needs no separate flag and no
                               workgroup barrier; twice the exchanged bytes; small messages only */
+    RAR_MODE_AUTO = 3      /* (default) RAR_MODE_FUSED_PACKED where it measured faster on MI355X: N a
+                              power of two and at most 1 MiB exchanged per step by all ranks together
+                              (P * chunk bytes); RAR_MODE_FUSED otherwise                          */
 } rar_mode;
 
 typedef enum rar_status {
@@ -116,8 +119,8 @@ int rar_plan_fold_partner(const rar_plan_t *plan, int rank);
 /* Element range of chunk c (0 <= c < G): *offset and *length (host, both required). */
 int rar_plan_chunk(const rar_plan_t *plan, int c, size_t *offset, size_t *length);
 
-/* Bytes of device scratch rar_allreduce needs: a 256-byte header (status word, sequence
- * number), the step barrier flags, the per-step partial buffers S_0..S_L of every rank
+/* Bytes of device scratch rar_allreduce needs: a 256-byte header (status word), the step
+ * barrier flags, the per-step partial buffers S_0..S_L of every rank
  * (Section 4.2.1: one buffer per inter-node step, so a rank may run ahead of its peer) and,
  * for chunks of at most 256 KiB, the per-step data+flag buffers of the packed mode. */
 size_t rar_plan_scratch_bytes(const rar_plan_t *plan);
@@ -128,11 +131,14 @@ size_t rar_plan_scratch_bytes(const rar_plan_t *plan);
  * header and flags with a fill kernel on its stream. */
 int rar_plan_set_scratch(rar_plan_t *plan, void *scratch, size_t bytes);
 
-/* Execution mode (default RAR_MODE_FUSED).  All modes produce identical bits.
+/* Execution mode (default RAR_MODE_AUTO).  All modes produce identical bits.
  * RAR_MODE_FUSED_PACKED is accepted only while a chunk is at most 256 KiB and N is a power of
- * two (RAR_ERR_LIMIT otherwise); rar_plan_scratch_bytes already includes its buffers for such plans. */
+ * two (RAR_ERR_LIMIT otherwise); rar_plan_scratch_bytes already includes its buffers for such plans.
+ * rar_plan_get_mode returns the mode as set; rar_plan_effective_mode the one a call would run
+ * (RAR_MODE_AUTO resolved to RAR_MODE_FUSED or RAR_MODE_FUSED_PACKED). */
 int rar_plan_set_mode(rar_plan_t *plan, int mode);
 int rar_plan_get_mode(const rar_plan_t *plan);
+int rar_plan_effective_mode(const rar_plan_t *plan);
 
 /* The paper's two hyper-parameters (Section 4.2.1, Appendix "Impact of Chunk Size and Block
  * Size"): B_s = workgroups per rank, C_s = bytes of a rank's chunk that one workgroup moves

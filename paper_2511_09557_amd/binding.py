@@ -10,7 +10,7 @@ import os
 from typing import Optional, Sequence
 
 RAR_BF16, RAR_F32 = 0, 1
-RAR_MODE_STEPWISE, RAR_MODE_FUSED, RAR_MODE_FUSED_PACKED = 0, 1, 2
+RAR_MODE_STEPWISE, RAR_MODE_FUSED, RAR_MODE_FUSED_PACKED, RAR_MODE_AUTO = 0, 1, 2, 3
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "librar.so")
@@ -53,6 +53,7 @@ def _load() -> ctypes.CDLL:
         "rar_plan_set_scratch": (ci, [vp, vp, sz]),
         "rar_plan_set_mode": (ci, [vp, ci]),
         "rar_plan_get_mode": (ci, [vp]),
+        "rar_plan_effective_mode": (ci, [vp]),
         "rar_plan_set_tuning": (ci, [vp, ci, sz]),
         "rar_plan_get_tuning": (ci, [vp, ctypes.POINTER(ci), ctypes.POINTER(sz)]),
         "rar_plan_set_wait_limit_us": (ci, [vp, ctypes.c_uint64]),
@@ -74,7 +75,7 @@ lib = _load()
 EXPORTS = ["rar_version", "rar_strerror", "rar_last_hip_error", "rar_plan", "rar_plan_free", "rar_plan_ranks",
            "rar_plan_nodes", "rar_plan_steps", "rar_plan_peer", "rar_plan_fold_partner", "rar_plan_chunk",
            "rar_plan_scratch_bytes", "rar_plan_set_scratch", "rar_plan_set_mode",
-           "rar_plan_get_mode", "rar_plan_set_tuning", "rar_plan_get_tuning",
+           "rar_plan_get_mode", "rar_plan_effective_mode", "rar_plan_set_tuning", "rar_plan_get_tuning",
            "rar_plan_set_wait_limit_us", "rar_plan_status", "rar_step_combine", "rar_allreduce",
            "rar_autotune", "rar_launch_floor", "rar_barrier_only", "rar_copy_probe"]
 
@@ -146,6 +147,10 @@ def rar_plan_get_mode(plan: int) -> int:
     return _check(lib.rar_plan_get_mode(plan), "rar_plan_get_mode")
 
 
+def rar_plan_effective_mode(plan: int) -> int:
+    return _check(lib.rar_plan_effective_mode(plan), "rar_plan_effective_mode")
+
+
 def rar_plan_set_tuning(plan: int, B_s: int, C_s: int) -> None:
     _check(lib.rar_plan_set_tuning(plan, B_s, C_s), "rar_plan_set_tuning")
 
@@ -201,7 +206,7 @@ class AllReduce:
     """A plan plus the torch tensor that backs its scratch.  torch supplies device memory and
     the current stream; every step of the all-reduce runs inside librar.so."""
 
-    def __init__(self, P: int, G: int, n: int, dtype: int, mode: int = RAR_MODE_FUSED, device="cuda:0"):
+    def __init__(self, P: int, G: int, n: int, dtype: int, mode: int = RAR_MODE_AUTO, device="cuda:0"):
         import torch
         self.P, self.G, self.n, self.dtype = P, G, n, dtype
         self.plan = rar_plan(P, G, n, dtype)
@@ -250,6 +255,9 @@ class AllReduce:
 
     def set_mode(self, mode: int) -> None:
         rar_plan_set_mode(self.plan, mode)
+
+    def effective_mode(self) -> int:
+        return rar_plan_effective_mode(self.plan)
 
     def set_tuning(self, B_s: int = 0, C_s: int = 0) -> None:
         rar_plan_set_tuning(self.plan, B_s, C_s)

@@ -111,7 +111,7 @@ int rar_allreduce(void *const *bufs, rar_plan_t *plan, void *stream) {
     }
     hipStream_t st = as_stream(stream);
     if (plan->mode == RAR_MODE_STEPWISE) return rar::launch_stepwise(*plan, ptrs, st);
-    const bool packed = plan->mode == RAR_MODE_FUSED_PACKED && g.L > 0;
+    const bool packed = rar::effective_mode(*plan) == RAR_MODE_FUSED_PACKED && g.L > 0;
     Tuning t;
     rc = fused_tuning(plan, packed, &t);
     if (rc != RAR_OK) return rc;
@@ -128,7 +128,7 @@ int rar_autotune(void *const *bufs, rar_plan_t *plan, void *stream, int calls, d
     if (plan->mode == RAR_MODE_STEPWISE) return RAR_ERR_ARG;
     int rc = ensure_residency(plan);
     if (rc != RAR_OK) return rc;
-    const bool packed = plan->mode == RAR_MODE_FUSED_PACKED && plan->geo.L > 0;
+    const bool packed = rar::effective_mode(*plan) == RAR_MODE_FUSED_PACKED && plan->geo.L > 0;
     const long *resident = packed ? plan->resident_packed : plan->resident;
     hipStream_t st = as_stream(stream);
     hipEvent_t e0, e1;
@@ -182,7 +182,7 @@ int rar_autotune(void *const *bufs, rar_plan_t *plan, void *stream, int calls, d
 int rar_launch_floor(rar_plan_t *plan, void *stream) {
     if (!plan) return RAR_ERR_ARG;
     Tuning t;
-    int rc = fused_tuning(plan, plan->mode == RAR_MODE_FUSED_PACKED && plan->geo.L > 0, &t);
+    int rc = fused_tuning(plan, rar::effective_mode(*plan) == RAR_MODE_FUSED_PACKED && plan->geo.L > 0, &t);
     if (rc != RAR_OK) return rc;
     return rar::launch_empty(static_cast<unsigned>(plan->geo.P) * t.B_s, as_stream(stream));
 }

@@ -454,11 +454,14 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(RankPtrs bufs, Shape s)
 // themselves: no separate flag, no wait for the stores to complete, no workgroup barrier; each
 // wavefront moves on as soon as its own 64 lanes have their words.  Twice the exchanged bytes.
 //
-// Scratch header: word 0 status, word 1 sequence number of the last finished call, word 2
-// count of workgroups that have finished the current call.  All workgroups read word 1 when
-// they start; the last one to finish stores the new number, so a number is never stored
-// before every workgroup of the launch has read the old one.  Keeping it on the device makes
-// the call replayable from a captured graph.
+// Where the sequence number comes from: every call makes every rank write every word position
+// of its buffers exactly once (the position of a word does not depend on B_s or C_s), so all
+// ranks' words at one position carry the same number after any history of calls.  A thread
+// therefore reads the number the previous call left in the first word it is about to
+// overwrite, adds one, and both stamps its own words with it and expects it in its peers'
+// words at the same positions.  No counter shared between workgroups, nothing to update when
+// the kernel ends, and a captured graph can replay the call.  Buffers start zero-filled; zero
+// is never used as a number.
 
 __device__ __forceinline__ u64 *packed_buf(const Shape &s, u32 level, u32 rank) {
     return reinterpret_cast<u64 *>(s.scratch + s.packed_offset +
@@ -529,9 +532,6 @@ __global__ __launch_bounds__(kThreads) void fused_packed_kernel(RankPtrs bufs, S
     const u32 whole_vecs = s.full_vecs > cbegin
                                ? (s.full_vecs - cbegin < valid_vecs ? static_cast<u32>(s.full_vecs - cbegin) : valid_vecs)
                                : 0u;
-    u32 *header = reinterpret_cast<u32 *>(s.scratch);
-    u32 seq = __hip_atomic_load(header + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u;
-    if (seq == 0u) seq = 1u;  // zero marks a word that was never written
     bool gave_up = false;
 
     for (u32 it = 0; it < s.iters; ++it) {
@@ -540,6 +540,15 @@ __global__ __launch_bounds__(kThreads) void fused_packed_kernel(RankPtrs bufs, S
         const u32 v0 = static_cast<u32>(first) + threadIdx.x;
         const bool whole = first + kThreads * U <= whole_vecs;
         const u32 valid = first < valid_vecs ? valid_vecs : 0u;
+        // the number of the previous call, from this thread's own first word of the slice (a
+        // thread without a word in this slice neither writes nor waits)
+        u32 seq = 0u;
+        if (s.L && (whole || v0 < valid)) {
+            const u64 *own = packed_buf(s, 0, p) + static_cast<u64>(slice) * (kThreads * U * 4) + threadIdx.x;
+            seq = static_cast<u32>(__hip_atomic_load(own, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >> 32);
+        }
+        seq += 1u;
+        if (seq == 0u) seq = 1u;  // zero marks a word that was never written
 
         uint4 part[U];
         reduce_scatter_slice<DT, GT, U>(bufs, s, r_n, c, v0, valid, whole, part);
@@ -555,15 +564,6 @@ __global__ __launch_bounds__(kThreads) void fused_packed_kernel(RankPtrs bufs, S
             }
         }
         all_gather_slice<DT, GT, U>(bufs, s, r_n, c, v0, valid, whole, part);
-    }
-
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        const u32 done = __hip_atomic_fetch_add(header + 2, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (done == gridDim.x - 1u) {
-            __hip_atomic_store(header + 2, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(header + 1, seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
     }
 }
 

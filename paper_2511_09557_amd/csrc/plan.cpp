@@ -205,7 +205,8 @@ int rar_plan_set_scratch(rar_plan_t *plan, void *scratch, size_t bytes) {
 
 int rar_plan_set_mode(rar_plan_t *plan, int mode) {
     if (!plan) return RAR_ERR_ARG;
-    if (mode != RAR_MODE_STEPWISE && mode != RAR_MODE_FUSED && mode != RAR_MODE_FUSED_PACKED) return RAR_ERR_ARG;
+    if (mode != RAR_MODE_STEPWISE && mode != RAR_MODE_FUSED && mode != RAR_MODE_FUSED_PACKED && mode != RAR_MODE_AUTO)
+        return RAR_ERR_ARG;
     // N = 1 has no exchange at all: the packed mode is then the plain fused kernel.
     if (mode == RAR_MODE_FUSED_PACKED && plan->geo.L > 0 && plan->geo.packed_offset == 0) return RAR_ERR_LIMIT;
     plan->mode = mode;
@@ -213,6 +214,8 @@ int rar_plan_set_mode(rar_plan_t *plan, int mode) {
 }
 
 int rar_plan_get_mode(const rar_plan_t *plan) { return plan ? plan->mode : RAR_ERR_ARG; }
+
+int rar_plan_effective_mode(const rar_plan_t *plan) { return plan ? rar::effective_mode(*plan) : RAR_ERR_ARG; }
 
 int rar_plan_set_tuning(rar_plan_t *plan, int B_s, size_t C_s) {
     if (!plan) return RAR_ERR_ARG;
@@ -226,7 +229,7 @@ int rar_plan_set_tuning(rar_plan_t *plan, int B_s, size_t C_s) {
 int rar_plan_get_tuning(const rar_plan_t *plan, int *B_s, size_t *C_s) {
     if (!plan || !B_s || !C_s) return RAR_ERR_ARG;
     const long *resident = !plan->have_resident ? nullptr
-                           : plan->mode == RAR_MODE_FUSED_PACKED ? plan->resident_packed : plan->resident;
+                           : rar::effective_mode(*plan) == RAR_MODE_FUSED_PACKED ? plan->resident_packed : plan->resident;
     rar::Tuning t = rar::resolve_tuning(*plan, resident);
     *B_s = t.B_s;
     *C_s = static_cast<size_t>(rar::kThreads) * 16 * t.unroll;

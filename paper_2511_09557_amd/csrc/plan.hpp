@@ -42,7 +42,7 @@ struct Geometry {
 
 struct rar_plan_s {
     rar::Geometry geo;
-    int mode = RAR_MODE_FUSED;
+    int mode = RAR_MODE_AUTO;
     int user_B_s = 0;          // 0 = built-in choice
     size_t user_C_s = 0;       // 0 = built-in choice
     uint64_t wait_limit_us = 5000000;
@@ -86,6 +86,18 @@ struct Tuning {
     int unroll;   // 16-byte vectors per thread per trip (C_s = kThreads * 16 * unroll)
     int iters;    // trips per workgroup: ceil(chunk_vecs / (B_s * kThreads * unroll))
 };
+
+// The mode a call runs in: RAR_MODE_AUTO takes the data+flag exchange while all ranks together
+// exchange at most 1 MiB per step (measured on MI355X: 8 KiB..1 MiB messages, P = 8..128: up to
+// there it is 5-25 % faster than the flag exchange, beyond it doubling the bytes costs more than
+// the flags), the flag exchange otherwise.
+constexpr size_t kAutoPackedMaxStepBytes = 1u << 20;
+inline int effective_mode(const rar_plan_t &plan) {
+    if (plan.mode != RAR_MODE_AUTO) return plan.mode;
+    const Geometry &g = plan.geo;
+    const bool small = static_cast<size_t>(g.P) * g.chunk_vecs * 16 <= kAutoPackedMaxStepBytes;
+    return g.L > 0 && g.packed_offset != 0 && small ? RAR_MODE_FUSED_PACKED : RAR_MODE_FUSED;
+}
 
 // Resolve the plan's tuning.  max_resident[i] = workgroups the device can hold at once for
 // the fused kernel with unroll 1 << i (nullptr or 0 = no residency limit, for host-only use).

@@ -53,7 +53,7 @@ int main(int argc, char **argv) {
     RAR_CHECK(rar_plan_set_scratch(plan, scratch, sbytes));
 
     int failures = 0;
-    for (int mode = RAR_MODE_STEPWISE; mode <= RAR_MODE_FUSED_PACKED; ++mode) {
+    for (int mode = RAR_MODE_STEPWISE; mode <= RAR_MODE_AUTO; ++mode) {
         int rc = rar_plan_set_mode(plan, mode);
         if (rc == RAR_ERR_LIMIT && mode == RAR_MODE_FUSED_PACKED) { printf("mode %d: not offered for this size\n", mode); continue; }
         RAR_CHECK(rc);

@@ -13,7 +13,7 @@ rar = pytest.importorskip("paper_2511_09557_amd") if torch.cuda.is_available() e
 
 DT = {"bf16": 0, "f32": 1}
 NP = {"bf16": np.uint16, "f32": np.float32}
-MODES = {"stepwise": 0, "fused": 1, "packed": 2}
+MODES = {"stepwise": 0, "fused": 1, "packed": 2, "auto": 3}
 
 
 def run_gpu(x: np.ndarray, G: int, mode: str, B_s: int = 0, C_s: int = 0, calls: int = 1) -> np.ndarray:
@@ -67,7 +67,7 @@ def test_step_combine_rejects_bad_arguments():
 
 # ---- the five workloads -------------------------------------------------------------------------
 
-@pytest.mark.parametrize("mode", ["stepwise", "fused", "packed"])
+@pytest.mark.parametrize("mode", ["stepwise", "fused", "packed", "auto"])
 @pytest.mark.parametrize("name", ["c1", "c1_int", "c2", "c3", "c4"])
 def test_workloads_bit_exact(name, mode):
     w = ri.WORKLOADS[name]
@@ -224,6 +224,7 @@ def test_edge_shapes(P, G, n, dtype):
     want = oracle.allreduce(x, G)
     assert_same_bits(run_gpu(x, G, "fused"), want, "fused")
     assert_same_bits(run_gpu(x, G, "stepwise"), want, "stepwise")
+    assert_same_bits(run_gpu(x, G, "auto"), want, "auto")
     N = P // G
     if N & (N - 1):
         # the data+flag mode is offered for N = 2^L only; several trips per workgroup instead
@@ -297,6 +298,28 @@ def test_repeated_calls_in_place():
     assert_same_bits(run_gpu(x, w.G, "stepwise", calls=3), want, "stepwise x3")
     assert_same_bits(run_gpu(x, w.G, "packed", calls=3), want, "packed x3")
     assert_same_bits(run_gpu(x, w.G, "packed", B_s=2, C_s=4096, calls=3), want, "packed x3, several trips")
+    assert_same_bits(run_gpu(x, w.G, "auto", calls=3), want, "auto x3")
+
+
+def test_packed_mode_alternating_with_flag_mode():
+    """One plan switched between the data+flag exchange and the flag exchange with changing launch
+    shapes: a word position's sequence number advances only in the calls that write it, and by
+    the same amount on every rank."""
+    w = ri.WORKLOADS["c2"]
+    x = ri.to_bf16_bits(ri.bf16_bits_to_f32(ri.make_inputs(w)) / 64.0)
+    ar = rar.AllReduce(w.P, w.G, w.n, 0, 2)
+    order = [(2, 0, 0), (1, 0, 0), (2, 3, 4096), (2, 1, 8192), (1, 2, 4096), (2, 16, 4096), (3, 0, 0), (2, 5, 16384),
+             (0, 0, 0), (2, 2, 32768), (2, 0, 0)]
+    want = oracle.allreduce(x, w.G, threads=8)
+    for k, (mode, B_s, C_s) in enumerate(order):
+        print(f"[gpu] alternating call {k}: mode {mode} B_s={B_s} C_s={C_s}", flush=True)
+        ar.set_mode(mode)
+        ar.set_tuning(B_s, C_s)
+        bufs = to_device(x)
+        ar(bufs)
+        assert ar.status() == 0
+        assert_same_bits(to_host(bufs, x.dtype), want, f"call {k}")
+    ar.close()
 
 
 def test_odd_node_count_under_replay():
@@ -362,7 +385,7 @@ def test_fused_equals_stepwise_under_replay():
     a.close(), b.close(), c.close()
 
 
-@pytest.mark.parametrize("mode", ["fused", "packed"])
+@pytest.mark.parametrize("mode", ["fused", "packed", "auto"])
 def test_graph_replay(mode):
     """The fused call inside a HIP graph, replayed with eager work in between."""
     w = ri.WORKLOADS["c2"]

@@ -153,7 +153,9 @@ def test_scratch_size_and_tuning():
     rar.rar_plan_set_mode(plan, 0)
     assert rar.rar_plan_get_mode(plan) == 0
     with pytest.raises(rar.RarError):
-        rar.rar_plan_set_mode(plan, 3)
+        rar.rar_plan_set_mode(plan, 4)
+    rar.rar_plan_set_mode(plan, 3)                  # automatic choice: 512 KiB chunks run the flag exchange
+    assert rar.rar_plan_get_mode(plan) == 3 and rar.rar_plan_effective_mode(plan) == 1
     with pytest.raises(rar.RarError) as e:          # 512 KiB chunks: too large for the packed mode
         rar.rar_plan_set_mode(plan, 2)
     assert e.value.status == -4
@@ -165,6 +167,20 @@ def test_scratch_size_and_tuning():
     with pytest.raises(rar.RarError):
         rar.rar_plan_set_scratch(plan, 0, 1 << 30)
     rar.rar_plan_free(plan)
+
+
+def test_automatic_mode():
+    """A new plan is in the automatic mode: the data+flag exchange while all ranks together
+    exchange at most 1 MiB per step and N is a power of two, the flag exchange otherwise."""
+    for P, G, nbytes, want in ((8, 4, 128 << 10, 2), (16, 4, 256 << 10, 2), (32, 4, 1 << 20, 1), (64, 4, 2 << 20, 1),
+                               (64, 4, 64 << 10, 2), (64, 4, 128 << 10, 1), (12, 4, 64 << 10, 1), (4, 4, 64 << 10, 1),
+                               (64, 8, 128 << 10, 2), (8, 1, 128 << 10, 2), (8, 1, 256 << 10, 1)):
+        plan = rar.rar_plan(P, G, nbytes // 2, 0)
+        assert rar.rar_plan_get_mode(plan) == 3
+        assert rar.rar_plan_effective_mode(plan) == want, (P, G, nbytes)
+        rar.rar_plan_set_mode(plan, 0)
+        assert rar.rar_plan_effective_mode(plan) == 0
+        rar.rar_plan_free(plan)
 
 
 def test_no_device_gives_an_error_not_a_crash():
