@@ -29,7 +29,7 @@ def _find(directory: str, suffix: str):
 
 def short(name: str) -> str:
     name = name.replace("void ", "")
-    for key in ("fused_kernel", "reduce_scatter_kernel", "exchange_sum_kernel", "all_gather_kernel",
+    for key in ("fused_packed_kernel", "fused_kernel", "fold_in_kernel", "reduce_scatter_kernel", "exchange_sum_kernel", "all_gather_kernel",
                 "combine_kernel", "copy_kernel", "fill_zero_kernel", "empty_kernel"):
         if key in name:
             args = name[name.find(key) + len(key):]
