@@ -125,6 +125,13 @@ int rar_plan_chunk(const rar_plan_t *plan, int c, size_t *offset, size_t *length
  * for chunks of at most 256 KiB, the per-step data+flag buffers of the packed mode. */
 size_t rar_plan_scratch_bytes(const rar_plan_t *plan);
 
+/* Where things live inside the scratch, as byte offsets and sizes (host pointers, each may be
+ * NULL): the step-barrier flags (32-bit counters, one per (buffer S_l, rank, workgroup slot))
+ * and the data+flag buffers of RAR_MODE_FUSED_PACKED (8-byte words, sequence number in the upper
+ * half; size 0 if the plan has none).  For tests and tools that inspect or preset them. */
+int rar_plan_scratch_layout(const rar_plan_t *plan, size_t *flags_offset, size_t *flags_bytes,
+                            size_t *packed_offset, size_t *packed_bytes);
+
 /* Lend `bytes` of device memory at `scratch` (256-byte aligned, >= rar_plan_scratch_bytes)
  * to the plan.  The plan borrows it until rar_plan_free or the next set_scratch; the caller
  * frees it afterwards.  Contents need no initialisation: the first all-reduce clears the

@@ -50,6 +50,7 @@ def _load() -> ctypes.CDLL:
         "rar_plan_fold_partner": (ci, [vp, ci]),
         "rar_plan_chunk": (ci, [vp, ci, ctypes.POINTER(sz), ctypes.POINTER(sz)]),
         "rar_plan_scratch_bytes": (sz, [vp]),
+        "rar_plan_scratch_layout": (ci, [vp, ctypes.POINTER(sz), ctypes.POINTER(sz), ctypes.POINTER(sz), ctypes.POINTER(sz)]),
         "rar_plan_set_scratch": (ci, [vp, vp, sz]),
         "rar_plan_set_mode": (ci, [vp, ci]),
         "rar_plan_get_mode": (ci, [vp]),
@@ -74,7 +75,7 @@ def _load() -> ctypes.CDLL:
 lib = _load()
 EXPORTS = ["rar_version", "rar_strerror", "rar_last_hip_error", "rar_plan", "rar_plan_free", "rar_plan_ranks",
            "rar_plan_nodes", "rar_plan_steps", "rar_plan_peer", "rar_plan_fold_partner", "rar_plan_chunk",
-           "rar_plan_scratch_bytes", "rar_plan_set_scratch", "rar_plan_set_mode",
+           "rar_plan_scratch_bytes", "rar_plan_scratch_layout", "rar_plan_set_scratch", "rar_plan_set_mode",
            "rar_plan_get_mode", "rar_plan_effective_mode", "rar_plan_set_tuning", "rar_plan_get_tuning",
            "rar_plan_set_wait_limit_us", "rar_plan_status", "rar_step_combine", "rar_allreduce",
            "rar_autotune", "rar_launch_floor", "rar_barrier_only", "rar_copy_probe"]
@@ -133,6 +134,13 @@ def rar_plan_chunk(plan: int, c: int):
 
 def rar_plan_scratch_bytes(plan: int) -> int:
     return lib.rar_plan_scratch_bytes(plan)
+
+
+def rar_plan_scratch_layout(plan: int):
+    """(flags_offset, flags_bytes, packed_offset, packed_bytes) inside the scratch."""
+    v = [ctypes.c_size_t() for _ in range(4)]
+    _check(lib.rar_plan_scratch_layout(plan, *[ctypes.byref(x) for x in v]), "rar_plan_scratch_layout")
+    return tuple(x.value for x in v)
 
 
 def rar_plan_set_scratch(plan: int, scratch_ptr: int, nbytes: int) -> None:
@@ -216,6 +224,7 @@ class AllReduce:
             base = self.scratch.data_ptr()
             aligned = (base + 255) // 256 * 256
             rar_plan_set_scratch(self.plan, aligned, nbytes)
+            self.scratch_base = aligned - base      # offset of the plan's scratch inside self.scratch
             rar_plan_set_mode(self.plan, mode)
         except Exception:
             rar_plan_free(self.plan)

@@ -191,6 +191,17 @@ int rar_plan_chunk(const rar_plan_t *plan, int c, size_t *offset, size_t *length
 
 size_t rar_plan_scratch_bytes(const rar_plan_t *plan) { return plan ? plan->geo.scratch_bytes : 0; }
 
+int rar_plan_scratch_layout(const rar_plan_t *plan, size_t *flags_offset, size_t *flags_bytes,
+                            size_t *packed_offset, size_t *packed_bytes) {
+    if (!plan) return RAR_ERR_ARG;
+    const Geometry &g = plan->geo;
+    if (flags_offset) *flags_offset = g.flags_offset;
+    if (flags_bytes) *flags_bytes = g.flags_bytes;
+    if (packed_offset) *packed_offset = g.packed_offset;
+    if (packed_bytes) *packed_bytes = g.packed_offset ? g.scratch_bytes - g.packed_offset : 0;
+    return RAR_OK;
+}
+
 int rar_plan_set_scratch(rar_plan_t *plan, void *scratch, size_t bytes) {
     if (!plan) return RAR_ERR_ARG;
     if (!scratch || bytes < plan->geo.scratch_bytes ||

@@ -301,6 +301,41 @@ def test_repeated_calls_in_place():
     assert_same_bits(run_gpu(x, w.G, "auto", calls=3), want, "auto x3")
 
 
+@pytest.mark.parametrize("mode", ["fused", "packed"])
+def test_sequence_numbers_wrap(mode):
+    """The step-barrier counters (flag exchange) and the sequence numbers in the exchanged words
+    (data+flag exchange) are 32-bit and only ever grow: preset them just below 2^32, the same on all
+    ranks as any history of calls leaves them, and run calls across the wrap."""
+    w = ri.WORKLOADS["c2"]
+    x = ri.to_bf16_bits(ri.bf16_bits_to_f32(ri.make_inputs(w)) / 64.0)
+    want = oracle.allreduce(x, w.G, threads=8)
+    ar = rar.AllReduce(w.P, w.G, w.n, 0, MODES[mode])
+    ar.set_tuning(2, 4096)                       # 8 trips per workgroup: the counters move 8 per call
+    bufs = to_device(x)
+    ar(bufs)                                     # first call: clears flags and words
+    assert ar.status() == 0
+    f_off, f_bytes, p_off, p_bytes = rar.rar_plan_scratch_layout(ar.plan)
+    base = ar.scratch_base
+    if mode == "fused":
+        flags = ar.scratch[base + f_off: base + f_off + f_bytes].view(torch.int32)
+        flags.fill_(-20)                         # 0xFFFFFFEC: wraps during the third call
+    else:
+        assert p_bytes > 0
+        words = ar.scratch[base + p_off: base + p_off + p_bytes].view(torch.int64)
+        words.fill_(-3 << 32)                    # sequence number 0xFFFFFFFD in every word: next calls use ..FE, ..FF, then 1
+    torch.cuda.synchronize()
+    for k in range(6):
+        print(f"[gpu] wrap {mode} call {k}", flush=True)
+        bufs = to_device(x)
+        ar(bufs)
+        assert ar.status() == 0
+        assert_same_bits(to_host(bufs, x.dtype), want, f"{mode} call {k} across the wrap")
+    if mode == "packed":
+        seq = (words[0].item() >> 32) & 0xFFFFFFFF
+        assert seq == 4, seq                     # ..FE, ..FF, (0 skipped) 1, 2, 3, 4
+    ar.close()
+
+
 def test_packed_mode_alternating_with_flag_mode():
     """One plan switched between the data+flag exchange and the flag exchange with changing launch
     shapes: a word position's sequence number advances only in the calls that write it, and by

@@ -169,6 +169,20 @@ def test_scratch_size_and_tuning():
     rar.rar_plan_free(plan)
 
 
+def test_scratch_layout():
+    plan = rar.rar_plan(16, 4, 131072, 0)
+    f_off, f_bytes, p_off, p_bytes = rar.rar_plan_scratch_layout(plan)
+    total = rar.rar_plan_scratch_bytes(plan)
+    L = rar.rar_plan_steps(plan)
+    assert f_off == 256 and f_bytes >= (L + 1) * 16 * 256 * 4
+    assert p_off >= f_off + f_bytes + (L + 1) * 16 * 65536 and p_off + p_bytes == total
+    assert p_bytes >= L * 16 * 2 * 65536            # twice a chunk per (step, rank)
+    rar.rar_plan_free(plan)
+    big = rar.rar_plan(64, 4, 1048576, 0)           # 512 KiB chunks: no data+flag buffers
+    assert rar.rar_plan_scratch_layout(big)[2:] == (0, 0)
+    rar.rar_plan_free(big)
+
+
 def test_automatic_mode():
     """A new plan is in the automatic mode: the data+flag exchange while all ranks together
     exchange at most 1 MiB per step and N is a power of two, the flag exchange otherwise."""
