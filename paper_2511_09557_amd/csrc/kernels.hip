@@ -10,6 +10,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <mutex>
 
 #include "launch.hpp"
 
@@ -756,9 +757,11 @@ const char *last_hip_error_string() { return g_last_hip_error == hipSuccess ? "n
 int device_info(DeviceInfo *out) {
     static DeviceInfo cached[16];
     static bool have[16] = {};
+    static std::mutex guard;  // plans of different threads may ask at the same time
     int dev = 0;
     if (note_hip(hipGetDevice(&dev)) != hipSuccess) return RAR_ERR_HIP;
     if (dev < 0 || dev >= 16) return RAR_ERR_HIP;
+    std::lock_guard<std::mutex> lock(guard);
     if (!have[dev]) {
         int cus = 0;
         if (note_hip(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess || cus < 1)
