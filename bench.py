@@ -176,7 +176,9 @@ def bench_workload(name: str, warmup: int, steps: int, extras: bool):
         def mm_then_ar(st):
             torch.matmul(a_mat, w_mat, out=o_mat)
             ar.launch(st)
+        ar.set_mode(rar.RAR_MODE_AUTO)      # as a caller who sets nothing would run it
         both = time_graph(mm_then_ar, 100, 2, 10)
+        ar.set_mode(rar.RAR_MODE_FUSED)
         out["graph100_matmul_us"] = mm
         out["graph100_interleaved_allreduce_us"] = both - mm
         del a_mat, w_mat, o_mat
