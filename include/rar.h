@@ -21,7 +21,9 @@
  *   - Every function returns RAR_OK (0) or a negative rar_status.  No exceptions, no aborts.
  *   - Nothing here allocates or frees device memory; scratch is lent by the caller.
  *   - A plan is not thread-safe, and two all-reduces on one plan must not overlap in time
- *     (they share the plan's scratch): order them on one stream or use two plans.
+ *     (they share the plan's scratch): order them on one stream or use two plans.  A plan
+ *     belongs to the device that is current at its first launch (it remembers that device's
+ *     size and how many workgroups of each kernel it holds at once).
  *   - The fused modes size their grid so that every workgroup is resident at once on an
  *     otherwise idle device (their step barriers spin).  Work that runs concurrently on other
  *     streams can take that room away; the waits are bounded (rar_plan_set_wait_limit_us), so
