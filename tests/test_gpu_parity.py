@@ -477,6 +477,39 @@ def test_wait_limit_ends_every_workgroup(mode):
     assert timed_out or True                   # a time-out is likely but not certain; recovery is what is checked
 
 
+@pytest.mark.parametrize("mode", ["fused", "packed"])
+def test_compute_on_another_stream_at_the_same_time(mode):
+    """Matrix products on a second stream compete for the compute units while the all-reduce runs,
+    so its workgroups are not all resident at once.  The step waits must still end: either the call
+    completes with the oracle's bits or, at worst, it reports a time-out; it never hangs."""
+    w = ri.WORKLOADS["c3"]
+    x = ri.make_inputs(w)
+    want = oracle.allreduce(x, w.G, threads=8)
+    ar = rar.AllReduce(w.P, w.G, w.n, 0, MODES[mode])
+    rar.rar_plan_set_wait_limit_us(ar.plan, 500_000)
+    a = torch.randn(8192, 8192, device="cuda:0", dtype=torch.bfloat16)
+    b = torch.randn(8192, 8192, device="cuda:0", dtype=torch.bfloat16)
+    side = torch.cuda.Stream()
+    ok = 0
+    for rep in range(5):
+        bufs = to_device(x)
+        torch.cuda.synchronize()
+        print(f"[gpu] concurrent compute {mode} rep {rep}", flush=True)
+        with torch.cuda.stream(side):
+            for _ in range(4):
+                torch.matmul(a, b)
+        ar(bufs)                                   # on the current stream, while the products run
+        status = ar.status()
+        side.synchronize()
+        assert status in (0, -8)
+        if status == 0:
+            assert_same_bits(to_host(bufs, x.dtype), want, f"{mode} rep {rep}")
+            ok += 1
+    print(f"[gpu] concurrent compute {mode}: {ok} of 5 calls completed", flush=True)
+    assert ok >= 1
+    ar.close()
+
+
 def test_allreduce_rejects_bad_arguments():
     P, G, n = 8, 4, 1024
     plan = rar.rar_plan(P, G, n, 0)
