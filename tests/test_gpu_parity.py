@@ -474,7 +474,7 @@ def test_wait_limit_ends_every_workgroup(mode):
     ar(bufs)
     assert ar.status() == 0
     assert_same_bits(to_host(bufs, x.dtype), want, "after a time-out")
-    assert timed_out or True                   # a time-out is likely but not certain; recovery is what is checked
+    print(f"[gpu] wait-limit run: time-out seen = {timed_out}", flush=True)   # likely, not certain; recovery is what is checked
 
 
 @pytest.mark.parametrize("mode", ["fused", "packed"])
