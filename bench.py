@@ -163,25 +163,28 @@ def bench_workload(name: str, warmup: int, steps: int, extras: bool):
         out["graph100_stepwise_us"] = time_graph(lambda st: ar.launch(st), 100, 2, 10)
         ar.set_mode(rar.RAR_MODE_FUSED)
         # back-to-back calls versus calls with compute in between (the paper's Appendix B runs a
-        # synthetic matmul between all-reduces): tokens x hidden @ hidden x hidden in bf16, then
-        # the all-reduce; the all-reduce's share is the difference to the matmuls alone
+        # synthetic matmul between all-reduces).  The compute here is what precedes the all-reduce
+        # in a tensor-parallel layer: every rank's row-parallel product, tokens x hidden/P @
+        # hidden/P x hidden in bf16, written straight into that rank's message (one batched product
+        # for all P emulated ranks; its weights, hidden x hidden in total, sweep the caches).  The
+        # all-reduce's share is the difference to the products alone.
         hidden = 8192 if w.bytes_per_rank <= (256 << 10) else 16384
         tokens = max(w.n // hidden, 1)
-        a_mat = torch.randn(tokens, hidden, device="cuda:0", dtype=torch.bfloat16)
-        w_mat = torch.randn(hidden, hidden, device="cuda:0", dtype=torch.bfloat16)
-        o_mat = torch.empty(tokens, hidden, device="cuda:0", dtype=torch.bfloat16)
-        torch.matmul(a_mat, w_mat, out=o_mat)
-        mm = time_graph(lambda st: torch.matmul(a_mat, w_mat, out=o_mat), 100, 2, 10)
+        whole = bufs[0]._base.view(w.P, tokens, hidden)
+        a_sh = torch.randn(w.P, tokens, hidden // w.P, device="cuda:0", dtype=torch.bfloat16)
+        w_sh = torch.randn(w.P, hidden // w.P, hidden, device="cuda:0", dtype=torch.bfloat16) / hidden ** 0.5
+        torch.bmm(a_sh, w_sh, out=whole)
+        mm = time_graph(lambda st: torch.bmm(a_sh, w_sh, out=whole), 100, 2, 10)
 
         def mm_then_ar(st):
-            torch.matmul(a_mat, w_mat, out=o_mat)
+            torch.bmm(a_sh, w_sh, out=whole)
             ar.launch(st)
         ar.set_mode(rar.RAR_MODE_AUTO)      # as a caller who sets nothing would run it
         both = time_graph(mm_then_ar, 100, 2, 10)
         ar.set_mode(rar.RAR_MODE_FUSED)
         out["graph100_matmul_us"] = mm
         out["graph100_interleaved_allreduce_us"] = both - mm
-        del a_mat, w_mat, o_mat
+        del a_sh, w_sh, whole
         # the data+flag ("packed") exchange of Section 4.2.2, where the planner offers it
         try:
             ar.set_mode(rar.RAR_MODE_FUSED_PACKED)
