@@ -140,6 +140,7 @@ struct Shape {
     u32 chunk_vecs;          // vectors per full chunk
     u32 full_vecs;           // whole vectors in a message
     u32 tail;                // elements in the partial last vector (0 = none)
+    u32 flag_stride;         // 32-bit words between the flags of consecutive workgroup slots
     u32 B_s;                 // workgroups per rank
     u32 iters;               // trips per workgroup
 };
@@ -300,9 +301,13 @@ __device__ __forceinline__ void load_slice_coherent(__amdgpu_buffer_rsrc_t S, u3
 // only ever grows (the paper's sequence number: flags are never cleared between calls), so a
 // consumer waits for "at least the value of my own trip", compared as a signed difference.
 
+// A (buffer, rank) owns kMaxWorkgroupsPerRank words, and a launch spreads its B_s flags over them
+// (flags that share a cache line serialise their stores and polls).  The spacing may change from
+// call to call: whichever word a launch uses, it uses for every buffer and every rank and stamps
+// with the same tickets, so all copies of one word index always hold the same count.
 __device__ __forceinline__ u32 *flag_ptr(const Shape &s, u32 level, u32 rank, u32 slot) {
     u32 *flags = reinterpret_cast<u32 *>(s.scratch + s.flags_offset);
-    return flags + (static_cast<u64>(level) * s.P + rank) * kMaxWorkgroupsPerRank + slot;
+    return flags + (static_cast<u64>(level) * s.P + rank) * kMaxWorkgroupsPerRank + slot * s.flag_stride;
 }
 
 // The workgroup's stores to S were issued at device scope; once every wave has seen them
@@ -694,6 +699,12 @@ static Shape make_shape(const rar_plan_t &plan, const Tuning &t) {
     s.tail = static_cast<u32>(g.n % g.per_vec);
     s.B_s = t.B_s;
     s.iters = t.iters;
+    // One flag per 64 bytes where the words allow it (measured: barrier time -15..25 %, whole call
+    // -1..3 % from 256 workgroups up; small grids are better off with 32 bytes).
+    const u32 widest = static_cast<u32>(g.P) * t.B_s >= 256u ? 16u : 8u;
+    u32 stride = 1;
+    while (stride < widest && stride * 2u * t.B_s <= static_cast<u32>(kMaxWorkgroupsPerRank)) stride *= 2u;
+    s.flag_stride = stride;
     return s;
 }
 
