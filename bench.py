@@ -83,6 +83,36 @@ def time_graph(enqueue, calls_per_graph: int, warmup: int, replays: int) -> floa
     return e0.elapsed_time(e1) * 1000.0 / (replays * calls_per_graph)
 
 
+def time_graph_two_chains(enqueue_a, enqueue_b, calls_per_chain: int, warmup: int, replays: int) -> float:
+    """Mean microseconds per call when two independent chains of calls (two plans, two sets of
+    buffers) run side by side on two streams inside one HIP graph: a call of one chain may start
+    while a call of the other is still finishing."""
+    import torch
+    main, side = torch.cuda.Stream(), torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(main):
+        enqueue_a(main)
+        enqueue_b(main)
+        main.synchronize()
+        with torch.cuda.graph(graph, stream=main):
+            side.wait_stream(main)
+            for _ in range(calls_per_chain):
+                enqueue_a(main)
+                enqueue_b(side)
+            main.wait_stream(side)
+    torch.cuda.synchronize()
+    for _ in range(warmup):
+        graph.replay()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(replays):
+        graph.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1000.0 / (replays * 2 * calls_per_chain)
+
+
 def copy_probe(times: int = 3) -> None:
     """Launch the library's plain copy kernel on COPY_PROBE_BYTES (so that a rocprofv3 --pmc run
     of this script sees a kernel whose HBM traffic is known: that many bytes read and written)."""
@@ -196,6 +226,18 @@ def bench_workload(name: str, warmup: int, steps: int, extras: bool):
             out["graph100_packed_us"] = time_graph(lambda st: ar.launch(st), 100, 2, 10)
             out["packed_tuning"] = dict(zip(("B_s", "C_s"), ar.tuning()))
             ar.set_mode(rar.RAR_MODE_FUSED)
+        # two independent chains of calls side by side (two plans, two sets of buffers, two streams
+        # in one graph): what per-step buffers and sequence numbers buy in the paper, a call that
+        # starts before the previous one has finished everywhere, shows here as overlap of kernels
+        bufs_b = device_bufs(x)
+        ar_b = rar.AllReduce(w.P, w.G, w.n, dtype, rar.RAR_MODE_AUTO)
+        ar_b.bind(bufs_b)
+        ar.set_mode(rar.RAR_MODE_AUTO)
+        out["graph100_two_chains_us"] = time_graph_two_chains(lambda st: ar.launch(st), lambda st: ar_b.launch(st), 50, 2, 10)
+        assert ar.status() == 0 and ar_b.status() == 0
+        ar_b.close()
+        del bufs_b
+        ar.set_mode(rar.RAR_MODE_FUSED)
         # what a caller who sets nothing gets (the library's automatic choice between the two)
         ar.set_mode(rar.RAR_MODE_AUTO)
         packed = ar.effective_mode() == rar.RAR_MODE_FUSED_PACKED

@@ -477,6 +477,34 @@ def test_wait_limit_ends_every_workgroup(mode):
     print(f"[gpu] wait-limit run: time-out seen = {timed_out}", flush=True)   # likely, not certain; recovery is what is checked
 
 
+@pytest.mark.parametrize("mode", ["fused", "auto"])
+@pytest.mark.parametrize("name", ["c2", "c4"])
+def test_two_plans_on_two_streams(name, mode):
+    """Two independent all-reduces (two plans, two sets of buffers) enqueued on two streams so that
+    their kernels overlap: neither has all its workgroups resident, both must give the oracle's bits."""
+    w = ri.WORKLOADS[name]
+    xa = ri.make_inputs(w)
+    xb = np.ascontiguousarray(xa[::-1])           # the same rows in another rank order: another result
+    want_a, want_b = oracle.allreduce(xa, w.G, threads=8), oracle.allreduce(xb, w.G, threads=8)
+    a = rar.AllReduce(w.P, w.G, w.n, 0, MODES[mode])
+    b = rar.AllReduce(w.P, w.G, w.n, 0, MODES[mode])
+    for p in (a, b):
+        rar.rar_plan_set_wait_limit_us(p.plan, 2_000_000)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    for rep in range(3):
+        ba, bb = to_device(xa), to_device(xb)
+        a.bind(ba), b.bind(bb)
+        torch.cuda.synchronize()
+        print(f"[gpu] two plans {name} {mode} rep {rep}", flush=True)
+        for _ in range(1):
+            a.launch(s1)
+            b.launch(s2)
+        assert a.status(s1) == 0 and b.status(s2) == 0
+        assert_same_bits(to_host(ba, xa.dtype), want_a, "chain a")
+        assert_same_bits(to_host(bb, xb.dtype), want_b, "chain b")
+    a.close(), b.close()
+
+
 @pytest.mark.parametrize("mode", ["fused", "packed"])
 def test_compute_on_another_stream_at_the_same_time(mode):
     """Matrix products on a second stream compete for the compute units while the all-reduce runs,
