@@ -233,10 +233,13 @@ def bench_workload(name: str, warmup: int, steps: int, extras: bool):
         ar_b = rar.AllReduce(w.P, w.G, w.n, dtype, rar.RAR_MODE_AUTO)
         ar_b.bind(bufs_b)
         ar.set_mode(rar.RAR_MODE_AUTO)
+        rar.rar_plan_set_concurrency(ar.plan, 2)       # each chain sizes its grid for half the device
+        rar.rar_plan_set_concurrency(ar_b.plan, 2)
         out["graph100_two_chains_us"] = time_graph_two_chains(lambda st: ar.launch(st), lambda st: ar_b.launch(st), 50, 2, 10)
         assert ar.status() == 0 and ar_b.status() == 0
         ar_b.close()
         del bufs_b
+        rar.rar_plan_set_concurrency(ar.plan, 1)
         ar.set_mode(rar.RAR_MODE_FUSED)
         # what a caller who sets nothing gets (the library's automatic choice between the two)
         ar.set_mode(rar.RAR_MODE_AUTO)

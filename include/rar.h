@@ -25,10 +25,11 @@
  *     belongs to the device that is current at its first launch (it remembers that device's
  *     size and how many workgroups of each kernel it holds at once).
  *   - The fused modes size their grid so that every workgroup is resident at once on an
- *     otherwise idle device (their step barriers spin).  Work that runs concurrently on other
- *     streams can take that room away; the waits are bounded (rar_plan_set_wait_limit_us), so
- *     the call then ends with RAR_ERR_TIMEOUT instead of hanging.  RAR_MODE_STEPWISE has no
- *     such requirement.
+ *     otherwise idle device (their step barriers spin).  Other work on other streams may run at
+ *     the same time as long as it finishes by itself; several fused all-reduces at the same
+ *     time need rar_plan_set_concurrency.  All waits are bounded (rar_plan_set_wait_limit_us):
+ *     a call that cannot proceed ends with RAR_ERR_TIMEOUT instead of hanging.
+ *     RAR_MODE_STEPWISE has no such requirement.
  */
 #ifndef RAR_H
 #define RAR_H
@@ -157,6 +158,14 @@ int rar_plan_effective_mode(const rar_plan_t *plan);
  * that all P*B_s workgroups are resident at once (the step barriers need that). */
 int rar_plan_set_tuning(rar_plan_t *plan, int B_s, size_t C_s);
 int rar_plan_get_tuning(const rar_plan_t *plan, int *B_s, size_t *C_s);
+
+/* How many fused all-reduces (of different plans, on different streams) the caller lets run on
+ * the device at the same time: 1 (default) to 8.  The built-in B_s and the residency clamp then
+ * leave each plan 1/k of the device.  Two fused kernels that together exceed what the device
+ * holds can each keep workgroup slots the other one waits for; the waits are bounded, so such
+ * calls end in RAR_ERR_TIMEOUT rather than hang, but they do not complete.  Kernels that do not
+ * wait for anything (matrix products, copies) may share the device freely. */
+int rar_plan_set_concurrency(rar_plan_t *plan, int k);
 
 /* Upper bound on the time one step-barrier wait may take before the kernel gives up, in
  * microseconds (default 5,000,000).  A wait that gives up records RAR_ERR_TIMEOUT in the

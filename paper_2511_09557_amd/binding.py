@@ -57,6 +57,7 @@ def _load() -> ctypes.CDLL:
         "rar_plan_effective_mode": (ci, [vp]),
         "rar_plan_set_tuning": (ci, [vp, ci, sz]),
         "rar_plan_get_tuning": (ci, [vp, ctypes.POINTER(ci), ctypes.POINTER(sz)]),
+        "rar_plan_set_concurrency": (ci, [vp, ci]),
         "rar_plan_set_wait_limit_us": (ci, [vp, ctypes.c_uint64]),
         "rar_plan_status": (ci, [vp, vp]),
         "rar_step_combine": (ci, [vp, vp, sz, sz, ci, vp]),
@@ -77,7 +78,7 @@ EXPORTS = ["rar_version", "rar_strerror", "rar_last_hip_error", "rar_plan", "rar
            "rar_plan_nodes", "rar_plan_steps", "rar_plan_peer", "rar_plan_fold_partner", "rar_plan_chunk",
            "rar_plan_scratch_bytes", "rar_plan_scratch_layout", "rar_plan_set_scratch", "rar_plan_set_mode",
            "rar_plan_get_mode", "rar_plan_effective_mode", "rar_plan_set_tuning", "rar_plan_get_tuning",
-           "rar_plan_set_wait_limit_us", "rar_plan_status", "rar_step_combine", "rar_allreduce",
+           "rar_plan_set_concurrency", "rar_plan_set_wait_limit_us", "rar_plan_status", "rar_step_combine", "rar_allreduce",
            "rar_autotune", "rar_launch_floor", "rar_barrier_only", "rar_copy_probe"]
 
 
@@ -167,6 +168,10 @@ def rar_plan_get_tuning(plan: int):
     b, c = ctypes.c_int(), ctypes.c_size_t()
     _check(lib.rar_plan_get_tuning(plan, ctypes.byref(b), ctypes.byref(c)), "rar_plan_get_tuning")
     return b.value, c.value
+
+
+def rar_plan_set_concurrency(plan: int, k: int) -> None:
+    _check(lib.rar_plan_set_concurrency(plan, k), "rar_plan_set_concurrency")
 
 
 def rar_plan_set_wait_limit_us(plan: int, microseconds: int) -> None:

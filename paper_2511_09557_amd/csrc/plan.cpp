@@ -56,7 +56,7 @@ Tuning resolve_tuning(const rar_plan_t &plan, const long *max_resident) {
     auto cap_for = [&](int unroll_index) {
         long cap = kMaxWorkgroupsPerRank;
         if (max_resident && max_resident[unroll_index] > 0) {
-            long fit = max_resident[unroll_index] / g.P;
+            long fit = max_resident[unroll_index] / plan.concurrency / g.P;
             if (fit < 1) fit = 1;
             if (fit < cap) cap = fit;
         }
@@ -76,7 +76,7 @@ Tuning resolve_tuning(const rar_plan_t &plan, const long *max_resident) {
     // workgroups per compute unit (32 KiB trips when a rank reads at most two buffers per
     // element, so that a thread still has 16 loads in flight; half the workgroups when it
     // reads eight or more).
-    const long target = 4L * (plan.compute_units > 0 ? plan.compute_units : 256);
+    const long target = 4L * (plan.compute_units > 0 ? plan.compute_units : 256) / plan.concurrency;
     const long small_target = g.L >= 4 ? target / 2 : target;
     long grid_cap = kMaxWorkgroupsPerRank;  // workgroups per rank beyond which the built-in choice does not go
     Tuning t{};
@@ -244,6 +244,12 @@ int rar_plan_get_tuning(const rar_plan_t *plan, int *B_s, size_t *C_s) {
     rar::Tuning t = rar::resolve_tuning(*plan, resident);
     *B_s = t.B_s;
     *C_s = static_cast<size_t>(rar::kThreads) * 16 * t.unroll;
+    return RAR_OK;
+}
+
+int rar_plan_set_concurrency(rar_plan_t *plan, int k) {
+    if (!plan || k < 1 || k > 8) return RAR_ERR_ARG;
+    plan->concurrency = k;
     return RAR_OK;
 }
 

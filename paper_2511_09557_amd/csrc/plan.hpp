@@ -46,6 +46,7 @@ struct rar_plan_s {
     int user_B_s = 0;          // 0 = built-in choice
     size_t user_C_s = 0;       // 0 = built-in choice
     uint64_t wait_limit_us = 5000000;
+    int concurrency = 1;       // fused kernels of different plans the caller runs at the same time
     void *scratch = nullptr;   // device, borrowed
     size_t scratch_size = 0;
     bool flags_clean = false;  // header + flags zeroed since the last event that invalidated them

@@ -481,7 +481,8 @@ def test_wait_limit_ends_every_workgroup(mode):
 @pytest.mark.parametrize("name", ["c2", "c4"])
 def test_two_plans_on_two_streams(name, mode):
     """Two independent all-reduces (two plans, two sets of buffers) enqueued on two streams so that
-    their kernels overlap: neither has all its workgroups resident, both must give the oracle's bits."""
+    their kernels overlap, each plan told that it shares the device with one other (so that the
+    two grids together stay resident): both must give the oracle's bits."""
     w = ri.WORKLOADS[name]
     xa = ri.make_inputs(w)
     xb = np.ascontiguousarray(xa[::-1])           # the same rows in another rank order: another result
@@ -490,6 +491,7 @@ def test_two_plans_on_two_streams(name, mode):
     b = rar.AllReduce(w.P, w.G, w.n, 0, MODES[mode])
     for p in (a, b):
         rar.rar_plan_set_wait_limit_us(p.plan, 2_000_000)
+        rar.rar_plan_set_concurrency(p.plan, 2)
     s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
     for rep in range(3):
         ba, bb = to_device(xa), to_device(xb)

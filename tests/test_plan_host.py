@@ -169,6 +169,18 @@ def test_scratch_size_and_tuning():
     rar.rar_plan_free(plan)
 
 
+def test_concurrency_halves_the_grid():
+    plan = rar.rar_plan(64, 4, 1 << 24, 0)            # a long message: the built-in grid is 4 workgroups per compute unit
+    full = rar.rar_plan_get_tuning(plan)
+    rar.rar_plan_set_concurrency(plan, 2)
+    half = rar.rar_plan_get_tuning(plan)
+    assert half[0] * 2 == full[0] and half[1] == full[1]
+    for bad in (0, 9, -1):
+        with pytest.raises(rar.RarError):
+            rar.rar_plan_set_concurrency(plan, bad)
+    rar.rar_plan_free(plan)
+
+
 def test_scratch_layout():
     plan = rar.rar_plan(16, 4, 131072, 0)
     f_off, f_bytes, p_off, p_bytes = rar.rar_plan_scratch_layout(plan)
