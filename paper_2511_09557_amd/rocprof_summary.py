@@ -3,6 +3,7 @@
 usage:
   python -m paper_2511_09557_amd.rocprof_summary stats  <dir>                 # --kernel-trace --stats run
   python -m paper_2511_09557_amd.rocprof_summary pmc    <fetch_dir> <write_dir> [--json out.json --workload c4]
+  python -m paper_2511_09557_amd.rocprof_summary counters <dir> [<dir> ...]   # any --pmc runs: mean per dispatch
 
 `stats` prints calls / average / total duration per kernel from *kernel_stats.csv (or from
 *kernel_trace.csv if the stats file is absent).  `pmc` reads *counter_collection.csv of a
@@ -92,7 +93,28 @@ def pmc(fetch_dir: str, write_dir: str):
     return "\n".join(lines), result, scale
 
 
+def counters(directories) -> str:
+    """Mean value per dispatch of every counter found, per kernel (library kernels only)."""
+    acc = defaultdict(lambda: defaultdict(list))
+    for d in directories:
+        for f in _find(d, "counter_collection.csv"):
+            for r in csv.DictReader(open(f)):
+                acc[short(r["Kernel_Name"])][r["Counter_Name"]].append(float(r["Counter_Value"]))
+    names = sorted({c for k in acc.values() for c in k})
+    out = [f"{'kernel':40s} {'dispatches':>10s} " + " ".join(f"{c:>26s}" for c in names)]
+    for k in sorted(acc):
+        if not any(key in k for key in ("fused", "copy_kernel", "_kernel<")):
+            continue
+        n = max(len(v) for v in acc[k].values())
+        out.append(f"{k:40s} {n:10d} " + " ".join(
+            f"{(sum(acc[k][c]) / len(acc[k][c]) if acc[k].get(c) else float('nan')):26.1f}" for c in names))
+    return "\n".join(out)
+
+
 def main(argv) -> int:
+    if len(argv) >= 3 and argv[1] == "counters":
+        print(counters(argv[2:]))
+        return 0
     if len(argv) >= 3 and argv[1] == "stats":
         print(stats(argv[2]))
         return 0
