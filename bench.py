@@ -154,7 +154,7 @@ def measured_traffic(workload: str):
         return None
 
 
-def bench_workload(name: str, warmup: int, steps: int, extras: bool):
+def bench_workload(name: str, warmup: int, steps: int, extras: bool, mode: str = "fused"):
     import torch
     import paper_2511_09557_amd as rar
     import rar_inputs as ri
@@ -165,6 +165,8 @@ def bench_workload(name: str, warmup: int, steps: int, extras: bool):
            "algorithmic_bytes": algorithmic_bytes(w.P, w.G, w.N, w.bytes_per_rank)}
     bufs = device_bufs(x)
     ar = rar.AllReduce(w.P, w.G, w.n, dtype, rar.RAR_MODE_FUSED)
+    if mode != "fused":     # only with --no-extras: the headline call in another mode (for per-kernel profiles)
+        ar.set_mode({"stepwise": rar.RAR_MODE_STEPWISE, "packed": rar.RAR_MODE_FUSED_PACKED, "auto": rar.RAR_MODE_AUTO}[mode])
     ar.bind(bufs)
     cur = torch.cuda.current_stream().cuda_stream   # looked up once: the timed calls pass the handle
     wall, ev_ms = time_calls(lambda: ar.launch(cur), warmup, steps)
@@ -467,6 +469,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--workload", default="c4", choices=["c1", "c2", "c3", "c4"])
     ap.add_argument("--no-extras", action="store_true", help="only the headline workload, fused mode")
+    ap.add_argument("--mode", default="fused", choices=["fused", "stepwise", "packed", "auto"],
+                    help="with --no-extras: run the headline workload in this mode (the JSON line says which)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--sensitivity", metavar="OUT.md", help="run the B_s x C_s sensitivity study instead and write it to this file")
     ap.add_argument("--hierarchy", metavar="OUT.md", help="run the flat-versus-hierarchical study instead and write it to this file")
@@ -491,12 +495,15 @@ def main() -> int:
         hierarchy(args.hierarchy)
         return 0
 
-    head = bench_workload(args.workload, args.warmup, args.steps, extras=not args.no_extras)
+    if args.mode != "fused" and not args.no_extras:
+        print("bench.py: --mode needs --no-extras", file=sys.stderr)
+        return 2
+    head = bench_workload(args.workload, args.warmup, args.steps, extras=not args.no_extras, mode=args.mode)
     copy_probe()
     w = ri.WORKLOADS[args.workload]
     us = head["fused_us"]
     achieved = head["algorithmic_bytes"] / (us * 1e-6) / 1e9
-    traffic = measured_traffic(args.workload)
+    traffic = measured_traffic(args.workload) if args.mode == "fused" else None
     line = {
         "metric": "us per all-reduce at 128KB-2MB bf16 (P virtual ranks); achieved HBM GB/s vs peak",
         "value": us,
@@ -511,11 +518,11 @@ def main() -> int:
         "dtype": "f32",             # the additions are binary32; the messages are stored as bf16
         "storage_dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": f"{args.workload}: P={w.P} (G={w.G} x N={w.N}), {w.bytes_per_rank} B bf16 per rank, fused mode",
+        "config": {"workload": f"{args.workload}: P={w.P} (G={w.G} x N={w.N}), {w.bytes_per_rank} B bf16 per rank, {args.mode} mode",
                    "tuning": head["tuning"]},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
-                     "kernel": "fused_kernel", "algorithmic_bytes_per_launch": head["algorithmic_bytes"],
+                     "kernel": "fused_kernel" if args.mode == "fused" else args.mode, "algorithmic_bytes_per_launch": head["algorithmic_bytes"],
                      "avg_launch_us": us,
                      # the kernel moves fewer bytes than the schedule's algorithmic count (a rank's own
                      # partial stays in registers between steps, the last partial is never written out),
