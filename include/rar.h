@@ -53,9 +53,9 @@ typedef enum rar_mode {
                               data and the call's 4-byte sequence number (Section 4.2.2, the
                               low-latency payload), so a step needs no separate flag and no
                               workgroup barrier; twice the exchanged bytes; small messages only */
-    RAR_MODE_AUTO = 3      /* (default) RAR_MODE_FUSED_PACKED where it measured faster on MI355X: N a
-                              power of two and at most 1 MiB exchanged per step by all ranks together
-                              (P * chunk bytes); RAR_MODE_FUSED otherwise                          */
+    RAR_MODE_AUTO = 3      /* (default) RAR_MODE_FUSED_PACKED where it measured faster on MI355X: at most
+                              1 MiB exchanged per step by all ranks together (P * chunk bytes);
+                              RAR_MODE_FUSED otherwise                                             */
 } rar_mode;
 
 typedef enum rar_status {
@@ -97,7 +97,6 @@ const char *rar_last_hip_error(void);
  *   nodes (2i, 2i+1), i < r, pair up, the even one hands its reduce-scatter result to the odd
  *   one and sits out, the 2^L remaining nodes are renumbered (node 2i+1 -> i, node j >= 2r ->
  *   j - r) and run the L steps on those numbers, and the odd node hands the result back.
- *   RAR_MODE_FUSED_PACKED is not offered for such N.
  *   *out (host) receives a plan owned by the caller; release it with rar_plan_free.
  *   Touches no device.
  */
@@ -142,8 +141,8 @@ int rar_plan_scratch_layout(const rar_plan_t *plan, size_t *flags_offset, size_t
 int rar_plan_set_scratch(rar_plan_t *plan, void *scratch, size_t bytes);
 
 /* Execution mode (default RAR_MODE_AUTO).  All modes produce identical bits.
- * RAR_MODE_FUSED_PACKED is accepted only while a chunk is at most 256 KiB and N is a power of
- * two (RAR_ERR_LIMIT otherwise); rar_plan_scratch_bytes already includes its buffers for such plans.
+ * RAR_MODE_FUSED_PACKED is accepted only while a chunk is at most 256 KiB (RAR_ERR_LIMIT
+ * otherwise); rar_plan_scratch_bytes already includes its buffers for such plans.
  * rar_plan_get_mode returns the mode as set; rar_plan_effective_mode the one a call would run
  * (RAR_MODE_AUTO resolved to RAR_MODE_FUSED or RAR_MODE_FUSED_PACKED). */
 int rar_plan_set_mode(rar_plan_t *plan, int mode);

@@ -462,7 +462,9 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(RankPtrs bufs, Shape s)
 //
 // Where the sequence number comes from: every call makes every rank write every word position
 // of its buffers exactly once (the position of a word does not depend on B_s or C_s), so all
-// ranks' words at one position carry the same number after any history of calls.  A thread
+// ranks' words at one position carry the same number after any history of calls (if N is not a
+// power of two, a rank that sits out the steps writes only its first buffer and one that takes
+// a partner in also writes a last one, every call alike, and only those are read).  A thread
 // therefore reads the number the previous call left in the first word it is about to
 // overwrite, adds one, and both stamps its own words with it and expects it in its peers'
 // words at the same positions.  No counter shared between workgroups, nothing to update when
@@ -539,6 +541,7 @@ __global__ __launch_bounds__(kThreads) void fused_packed_kernel(RankPtrs bufs, S
                                ? (s.full_vecs - cbegin < valid_vecs ? static_cast<u32>(s.full_vecs - cbegin) : valid_vecs)
                                : 0u;
     bool gave_up = false;
+    const bool idle = sits_out(r_n, s.fold), takes_in = folds_in(r_n, s.fold);
 
     for (u32 it = 0; it < s.iters; ++it) {
         const u32 slice = w + it * s.B_s;
@@ -558,15 +561,26 @@ __global__ __launch_bounds__(kThreads) void fused_packed_kernel(RankPtrs bufs, S
 
         uint4 part[U];
         reduce_scatter_slice<DT, GT, U>(bufs, s, r_n, c, v0, valid, whole, part);
-        if (valid != 0u) {  // uniform over the workgroup; a slice past the chunk exchanges nothing
-            if (s.L) store_slice_packed<U>(packed_buf(s, 0, p), slice, v0, valid, whole, seq, part);
-            for (u32 l = 0; l < s.L; ++l) {
-                const u32 peer = (r_n ^ (1u << l)) * G + c;
+        if (valid != 0u && s.L) {  // uniform over the workgroup; a slice past the chunk exchanges nothing
+            if (takes_in) {  // the even partner's reduce-scatter result joins before the steps
                 uint4 got[U];
-                load_slice_packed<U>(s, packed_buf(s, l, peer), slice, v0, valid, whole, seq, gave_up, got);
+                load_slice_packed<U>(s, packed_buf(s, 0, p - G), slice, v0, valid, whole, seq, gave_up, got);
 #pragma unroll
                 for (int u = 0; u < U; ++u) part[u] = combine<DT>(got[u], part[u]);
-                if (l + 1 < s.L) store_slice_packed<U>(packed_buf(s, l + 1, p), slice, v0, valid, whole, seq, part);
+            }
+            store_slice_packed<U>(packed_buf(s, 0, p), slice, v0, valid, whole, seq, part);
+            if (idle) {  // no steps: the odd partner's last partial is the result
+                load_slice_packed<U>(s, packed_buf(s, s.L, p + G), slice, v0, valid, whole, seq, gave_up, part);
+            } else {
+                for (u32 l = 0; l < s.L; ++l) {
+                    const u32 peer = peer_node(r_n, l, s.fold) * G + c;
+                    uint4 got[U];
+                    load_slice_packed<U>(s, packed_buf(s, l, peer), slice, v0, valid, whole, seq, gave_up, got);
+#pragma unroll
+                    for (int u = 0; u < U; ++u) part[u] = combine<DT>(got[u], part[u]);
+                    if (l + 1 < s.L || takes_in)
+                        store_slice_packed<U>(packed_buf(s, l + 1, p), slice, v0, valid, whole, seq, part);
+                }
             }
         }
         all_gather_slice<DT, GT, U>(bufs, s, r_n, c, v0, valid, whole, part);

@@ -39,13 +39,15 @@ int make_geometry(int P, int G, size_t n, int dtype, Geometry *geo) {
     g.flags_bytes = round_up(static_cast<size_t>(L + 1) * P * kMaxWorkgroupsPerRank * 4, kAlign);
     g.data_offset = g.flags_offset + g.flags_bytes;
     g.scratch_bytes = g.data_offset + static_cast<size_t>(L + 1) * P * g.chunk_stride;
-    // Data+flag buffers for the packed exchange: one per (step l < L, rank), twice a chunk.
-    if (L > 0 && g.fold == 0 && g.chunk_vecs * 16 <= kPackedMaxChunkBytes) {
+    // Data+flag buffers for the packed exchange: one per (step l < L, rank), twice a chunk; one
+    // more per rank if N is not a power of two (the last partial goes back to a node that sat out).
+    if (L > 0 && g.chunk_vecs * 16 <= kPackedMaxChunkBytes) {
         g.packed_offset = g.scratch_bytes;
+        g.packed_levels = L + (g.fold ? 1 : 0);
         // whole slices of the largest trip (8 vectors per thread): the word layout inside a
         // slice is strided by thread, so a ragged last slice still spans its full extent
         g.packed_stride = round_up(g.chunk_vecs, static_cast<size_t>(kThreads) * 8) * 32;
-        g.scratch_bytes = g.packed_offset + static_cast<size_t>(L) * P * g.packed_stride;
+        g.scratch_bytes = g.packed_offset + static_cast<size_t>(g.packed_levels) * P * g.packed_stride;
     }
     *geo = g;
     return RAR_OK;

@@ -35,6 +35,7 @@ struct Geometry {
     size_t data_offset = 0;  // byte offset of S_0(rank 0)
     size_t packed_offset = 0;  // byte offset of the data+flag buffers (0 = the plan has none)
     size_t packed_stride = 0;  // bytes of one data+flag buffer: 2 * chunk bytes, rounded
+    int packed_levels = 0;     // data+flag buffers per rank: L, or L + 1 if N is not a power of two
     size_t scratch_bytes = 0;
 };
 

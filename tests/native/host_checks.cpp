@@ -32,7 +32,7 @@ static void check_shape(int P, int G, size_t n, int dtype) {
     CHECK(g.chunk_stride >= g.chunk_vecs * 16 && g.chunk_stride % 256 == 0);
     CHECK(g.flags_bytes >= static_cast<size_t>(g.L + 1) * P * rar::kMaxWorkgroupsPerRank * 4);
     CHECK(g.N == (1 << g.L) + g.fold && g.fold >= 0 && g.fold < (1 << g.L));
-    CHECK(g.fold == 0 || g.packed_offset == 0);
+    CHECK(g.packed_levels == (g.packed_offset ? g.L + (g.fold ? 1 : 0) : 0));
     CHECK(g.data_offset % 256 == 0);
     CHECK(g.scratch_bytes >= g.data_offset + static_cast<size_t>(g.L + 1) * P * g.chunk_stride);
     // peers: mutual, same local id; a node that sits out has a partner on the next node that
@@ -73,7 +73,7 @@ static void check_shape(int P, int G, size_t n, int dtype) {
                 if (g.packed_offset) {
                     const size_t slices_with_data = (g.chunk_vecs + slice - 1) / slice;
                     CHECK(slices_with_data * slice * 32 <= g.packed_stride);
-                    CHECK(g.scratch_bytes >= g.packed_offset + static_cast<size_t>(g.L) * P * g.packed_stride);
+                    CHECK(g.scratch_bytes >= g.packed_offset + static_cast<size_t>(g.packed_levels) * P * g.packed_stride);
                 }
                 if (resident[0]) {
                     const int idx = t.unroll == 1 ? 0 : t.unroll == 2 ? 1 : t.unroll == 4 ? 2 : 3;

@@ -227,10 +227,9 @@ def test_edge_shapes(P, G, n, dtype):
     assert_same_bits(run_gpu(x, G, "auto"), want, "auto")
     N = P // G
     if N & (N - 1):
-        # the data+flag mode is offered for N = 2^L only; several trips per workgroup instead
-        # (three or more make a workgroup reuse its two places in every partial buffer)
+        # several trips per workgroup (three or more make a workgroup reuse its two places in
+        # every partial buffer) with the hand-over before and after the steps
         assert_same_bits(run_gpu(x, G, "fused", B_s=1, C_s=4096, calls=1), want, "fused, one workgroup per rank")
-        return
     assert_same_bits(run_gpu(x, G, "packed"), want, "packed")
     assert_same_bits(run_gpu(x, G, "packed", B_s=1, C_s=4096), want, "packed, one workgroup per rank")
 
@@ -358,17 +357,20 @@ def test_packed_mode_alternating_with_flag_mode():
 
 
 def test_odd_node_count_under_replay():
-    """N = 6 nodes (outside the paper): 300 fused calls with fresh inputs and changing launch shapes
-    against the stepwise path; the hand-over before and after the steps uses the same flags."""
+    """N = 6 nodes (outside the paper): 300 calls of the flag exchange and of the data+flag exchange
+    with fresh inputs and changing launch shapes against the stepwise path; the hand-over before
+    and after the steps uses the same flags and sequence numbers as the steps."""
     P, G, n = 24, 4, 96 * 1024
     a = rar.AllReduce(P, G, n, 0, 1)
     b = rar.AllReduce(P, G, n, 0, 0)
+    c = rar.AllReduce(P, G, n, 0, 2)
     gen = torch.Generator(device="cuda:0")
     gen.manual_seed(4321)
     src = torch.empty(P, n, device="cuda:0", dtype=torch.bfloat16)
-    wa, wb = torch.empty_like(src), torch.empty_like(src)
+    wa, wb, wc = torch.empty_like(src), torch.empty_like(src), torch.empty_like(src)
     a.bind([wa[p] for p in range(P)])
     b.bind([wb[p] for p in range(P)])
+    c.bind([wc[p] for p in range(P)])
     print("[gpu] replay stress, N = 6", flush=True)
     shapes = [(0, 0), (2, 4096), (3, 4096), (1, 8192), (5, 16384), (1, 32768)]
     for it in range(300):
@@ -376,12 +378,15 @@ def test_odd_node_count_under_replay():
             src.copy_(torch.randn(P, n, device="cuda:0", generator=gen))
         else:
             src.mul_(0.5)
-        wa.copy_(src), wb.copy_(src)
+        wa.copy_(src), wb.copy_(src), wc.copy_(src)
         a.set_tuning(*shapes[(it // 3) % len(shapes)])
-        a.launch(), b.launch()
+        c.set_tuning(*shapes[(it // 7) % len(shapes)])
+        a.launch(), b.launch(), c.launch()
         assert torch.equal(wa.view(torch.int16), wb.view(torch.int16)), ("fused", it)
+        assert torch.equal(wc.view(torch.int16), wb.view(torch.int16)), ("packed", it)
         assert torch.equal(wb[P - 1].view(torch.int16), wb[0].view(torch.int16)), ("ranks differ", it)
-    assert a.status() == 0
+    assert a.status() == 0 and c.status() == 0
+    c.close()
     x = src.cpu().view(torch.int16).numpy().view(np.uint16)
     assert_same_bits(wb.cpu().view(torch.int16).numpy().view(np.uint16), oracle.allreduce(x, G, threads=8), "stepwise, last input")
     a.close(), b.close()
