@@ -34,9 +34,9 @@ int ensure_residency(rar_plan_t *plan) {
     if (got != RAR_OK) return got;
     plan->compute_units = info.compute_units;
     for (int i = 0; i < 4; ++i) {
-        int rc = rar::fused_max_resident(plan->geo.dtype, plan->geo.G, 1 << i, false, &plan->resident[i]);
+        int rc = rar::fused_max_resident(plan->geo.dtype, plan->geo.G, 1 << i, false, plan->geo.fold != 0, &plan->resident[i]);
         if (rc != RAR_OK) return rc;
-        rc = rar::fused_max_resident(plan->geo.dtype, plan->geo.G, 1 << i, true, &plan->resident_packed[i]);
+        rc = rar::fused_max_resident(plan->geo.dtype, plan->geo.G, 1 << i, true, plan->geo.fold != 0, &plan->resident_packed[i]);
         if (rc != RAR_OK) return rc;
     }
     plan->have_resident = true;

@@ -380,7 +380,8 @@ __device__ __forceinline__ void locate(const Shape &s, u32 block, u32 &r_n, u32 
 // a power of two, a rank that sits out publishes S_0 and all-gathers its partner's S_L, and the
 // partner adds that S_0 to its own before the steps and publishes S_L after them.
 // DATA = false leaves all data movement out (barrier traffic only, for measurement).
-template <int DT, int GT, int U, bool DATA>
+// FOLD = false compiles the hand-over for N that is not a power of two out (Algorithm 1 as it stands).
+template <int DT, int GT, int U, bool DATA, bool FOLD>
 __global__ __launch_bounds__(kThreads) void fused_kernel(RankPtrs bufs, Shape s) {
     u32 r_n, c, w;
     locate(s, blockIdx.x, r_n, c, w);
@@ -395,7 +396,8 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(RankPtrs bufs, Shape s)
     // this slot's counter as the previous call left it (all ranks' slot w hold the same value)
     const u32 base = s.L ? __hip_atomic_load(flag_ptr(s, 0, p, w), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
     bool gave_up = false;
-    const bool idle = sits_out(r_n, s.fold), takes_in = folds_in(r_n, s.fold);
+    const u32 fold = FOLD ? s.fold : 0u;
+    const bool idle = sits_out(r_n, fold), takes_in = folds_in(r_n, fold);
 
     for (u32 it = 0; it < s.iters; ++it) {
         const u32 slice = w + it * s.B_s;
@@ -433,7 +435,7 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(RankPtrs bufs, Shape s)
             if (DATA) load_slice_coherent<U>(partial_rsrc(s, s.L, p + G), s0, v0, valid, whole, part);
         } else {
             for (u32 l = 0; l < s.L; ++l) {
-                const u32 peer = peer_node(r_n, l, s.fold) * G + c;
+                const u32 peer = peer_node(r_n, l, fold) * G + c;
                 wait_for(s, flag_ptr(s, l, peer, w), ticket, gave_up);
                 if (DATA) {
                     uint4 got[U];
@@ -529,7 +531,7 @@ __device__ __forceinline__ void load_slice_packed(const Shape &s, const u64 *buf
     }
 }
 
-template <int DT, int GT, int U>
+template <int DT, int GT, int U, bool FOLD>
 __global__ __launch_bounds__(kThreads) void fused_packed_kernel(RankPtrs bufs, Shape s) {
     u32 r_n, c, w;
     locate(s, blockIdx.x, r_n, c, w);
@@ -541,7 +543,8 @@ __global__ __launch_bounds__(kThreads) void fused_packed_kernel(RankPtrs bufs, S
                                ? (s.full_vecs - cbegin < valid_vecs ? static_cast<u32>(s.full_vecs - cbegin) : valid_vecs)
                                : 0u;
     bool gave_up = false;
-    const bool idle = sits_out(r_n, s.fold), takes_in = folds_in(r_n, s.fold);
+    const u32 fold = FOLD ? s.fold : 0u;
+    const bool idle = sits_out(r_n, fold), takes_in = folds_in(r_n, fold);
 
     for (u32 it = 0; it < s.iters; ++it) {
         const u32 slice = w + it * s.B_s;
@@ -573,7 +576,7 @@ __global__ __launch_bounds__(kThreads) void fused_packed_kernel(RankPtrs bufs, S
                 load_slice_packed<U>(s, packed_buf(s, s.L, p + G), slice, v0, valid, whole, seq, gave_up, part);
             } else {
                 for (u32 l = 0; l < s.L; ++l) {
-                    const u32 peer = peer_node(r_n, l, s.fold) * G + c;
+                    const u32 peer = peer_node(r_n, l, fold) * G + c;
                     uint4 got[U];
                     load_slice_packed<U>(s, packed_buf(s, l, peer), slice, v0, valid, whole, seq, gave_up, got);
 #pragma unroll
@@ -724,51 +727,56 @@ static Shape make_shape(const rar_plan_t &plan, const Tuning &t) {
 
 typedef void (*FusedFn)(RankPtrs, Shape);
 
-template <int DT, int GT, bool DATA>
+// Kernels with the hand-over for N that is not a power of two exist for run-time G only: such
+// plans (outside the paper) all take the generic variant.
+template <int DT, int GT, bool DATA, bool FOLD>
 static FusedFn pick_unroll(int unroll) {
     switch (unroll) {
-        case 1: return fused_kernel<DT, GT, 1, DATA>;
-        case 2: return fused_kernel<DT, GT, 2, DATA>;
-        case 4: return fused_kernel<DT, GT, 4, DATA>;
-        default: return fused_kernel<DT, GT, 8, DATA>;
+        case 1: return fused_kernel<DT, GT, 1, DATA, FOLD>;
+        case 2: return fused_kernel<DT, GT, 2, DATA, FOLD>;
+        case 4: return fused_kernel<DT, GT, 4, DATA, FOLD>;
+        default: return fused_kernel<DT, GT, 8, DATA, FOLD>;
     }
 }
 template <int DT, bool DATA>
-static FusedFn pick_group(int G, int unroll) {
+static FusedFn pick_group(int G, int unroll, bool fold) {
+    if (fold) return pick_unroll<DT, 0, DATA, true>(unroll);
     switch (G) {
-        case 1: return pick_unroll<DT, 1, DATA>(unroll);
-        case 2: return pick_unroll<DT, 2, DATA>(unroll);
-        case 4: return pick_unroll<DT, 4, DATA>(unroll);
-        case 8: return pick_unroll<DT, 8, DATA>(unroll);
-        default: return pick_unroll<DT, 0, DATA>(unroll);
+        case 1: return pick_unroll<DT, 1, DATA, false>(unroll);
+        case 2: return pick_unroll<DT, 2, DATA, false>(unroll);
+        case 4: return pick_unroll<DT, 4, DATA, false>(unroll);
+        case 8: return pick_unroll<DT, 8, DATA, false>(unroll);
+        default: return pick_unroll<DT, 0, DATA, false>(unroll);
     }
 }
-static FusedFn pick_fused(int dtype, int G, int unroll, bool data) {
-    if (dtype == RAR_BF16) return data ? pick_group<RAR_BF16, true>(G, unroll) : pick_group<RAR_BF16, false>(G, unroll);
-    return data ? pick_group<RAR_F32, true>(G, unroll) : pick_group<RAR_F32, false>(G, unroll);
+static FusedFn pick_fused(int dtype, int G, int unroll, bool data, bool fold) {
+    if (dtype == RAR_BF16)
+        return data ? pick_group<RAR_BF16, true>(G, unroll, fold) : pick_group<RAR_BF16, false>(G, unroll, fold);
+    return data ? pick_group<RAR_F32, true>(G, unroll, fold) : pick_group<RAR_F32, false>(G, unroll, fold);
 }
 
-template <int DT, int GT>
+template <int DT, int GT, bool FOLD>
 static FusedFn pick_packed_unroll(int unroll) {
     switch (unroll) {
-        case 1: return fused_packed_kernel<DT, GT, 1>;
-        case 2: return fused_packed_kernel<DT, GT, 2>;
-        case 4: return fused_packed_kernel<DT, GT, 4>;
-        default: return fused_packed_kernel<DT, GT, 8>;
+        case 1: return fused_packed_kernel<DT, GT, 1, FOLD>;
+        case 2: return fused_packed_kernel<DT, GT, 2, FOLD>;
+        case 4: return fused_packed_kernel<DT, GT, 4, FOLD>;
+        default: return fused_packed_kernel<DT, GT, 8, FOLD>;
     }
 }
 template <int DT>
-static FusedFn pick_packed_group(int G, int unroll) {
+static FusedFn pick_packed_group(int G, int unroll, bool fold) {
+    if (fold) return pick_packed_unroll<DT, 0, true>(unroll);
     switch (G) {
-        case 1: return pick_packed_unroll<DT, 1>(unroll);
-        case 2: return pick_packed_unroll<DT, 2>(unroll);
-        case 4: return pick_packed_unroll<DT, 4>(unroll);
-        case 8: return pick_packed_unroll<DT, 8>(unroll);
-        default: return pick_packed_unroll<DT, 0>(unroll);
+        case 1: return pick_packed_unroll<DT, 1, false>(unroll);
+        case 2: return pick_packed_unroll<DT, 2, false>(unroll);
+        case 4: return pick_packed_unroll<DT, 4, false>(unroll);
+        case 8: return pick_packed_unroll<DT, 8, false>(unroll);
+        default: return pick_packed_unroll<DT, 0, false>(unroll);
     }
 }
-static FusedFn pick_packed(int dtype, int G, int unroll) {
-    return dtype == RAR_BF16 ? pick_packed_group<RAR_BF16>(G, unroll) : pick_packed_group<RAR_F32>(G, unroll);
+static FusedFn pick_packed(int dtype, int G, int unroll, bool fold) {
+    return dtype == RAR_BF16 ? pick_packed_group<RAR_BF16>(G, unroll, fold) : pick_packed_group<RAR_F32>(G, unroll, fold);
 }
 
 // The most recent failing HIP status seen by the library on this thread (for rar_last_hip_error).
@@ -798,12 +806,12 @@ int device_info(DeviceInfo *out) {
     return RAR_OK;
 }
 
-int fused_max_resident(int dtype, int G, int unroll, bool packed, long *out) {
+int fused_max_resident(int dtype, int G, int unroll, bool packed, bool fold, long *out) {
     DeviceInfo info;
     int rc = device_info(&info);
     if (rc != RAR_OK) return rc;
     int per_cu = 0;
-    FusedFn fn = packed ? pick_packed(dtype, G, unroll) : pick_fused(dtype, G, unroll, true);
+    FusedFn fn = packed ? pick_packed(dtype, G, unroll, fold) : pick_fused(dtype, G, unroll, true, fold);
     if (note_hip(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(fn), kThreads, 0)) !=
             hipSuccess || per_cu < 1)
         return RAR_ERR_HIP;
@@ -831,7 +839,7 @@ int launch_fused(const rar_plan_t &plan, const RankPtrs &bufs, const Tuning &t, 
     const Geometry &g = plan.geo;
     const Shape s = make_shape(plan, t);
     const u32 grid = static_cast<u32>(g.P) * t.B_s;
-    FusedFn fn = pick_fused(g.dtype, g.G, t.unroll, data);
+    FusedFn fn = pick_fused(g.dtype, g.G, t.unroll, data, g.fold != 0);
     fn<<<dim3(grid), dim3(kThreads), 0, stream>>>(bufs, s);
     return check_launch();
 }
@@ -841,7 +849,7 @@ int launch_fused_packed(const rar_plan_t &plan, const RankPtrs &bufs, const Tuni
     const Geometry &g = plan.geo;
     const Shape s = make_shape(plan, t);
     const u32 grid = static_cast<u32>(g.P) * t.B_s;
-    FusedFn fn = pick_packed(g.dtype, g.G, t.unroll);
+    FusedFn fn = pick_packed(g.dtype, g.G, t.unroll, g.fold != 0);
     fn<<<dim3(grid), dim3(kThreads), 0, stream>>>(bufs, s);
     return check_launch();
 }

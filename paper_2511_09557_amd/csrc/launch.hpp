@@ -23,8 +23,9 @@ int device_info(DeviceInfo *out);
 hipError_t note_hip(hipError_t e);
 const char *last_hip_error_string();
 
-// Workgroups of the fused kernel (dtype, G, unroll) the current device can hold at once.
-int fused_max_resident(int dtype, int G, int unroll, bool packed, long *out);
+// Workgroups of the fused kernel (dtype, G, unroll; fold = the variant for N that is not a power
+// of two) the current device can hold at once.
+int fused_max_resident(int dtype, int G, int unroll, bool packed, bool fold, long *out);
 
 int launch_fill_zero(void *words, size_t bytes, hipStream_t stream);
 int launch_fused(const rar_plan_t &plan, const RankPtrs &bufs, const Tuning &t, bool data, hipStream_t stream);
