@@ -382,8 +382,10 @@ __device__ __forceinline__ void locate(const Shape &s, u32 block, u32 &r_n, u32 
 // DATA = false leaves all data movement out (barrier traffic only, for measurement).
 // FOLD = false compiles the hand-over for N that is not a power of two out (Algorithm 1 as it
 // stands); ONE = true is the launch in which every workgroup makes a single trip (no loop, no
-// reuse of places): measured 1-5 % faster than leaving both to run-time branches.
-template <int DT, int GT, int U, bool DATA, bool FOLD, bool ONE>
+// reuse of places); FULL = true the launch whose slices are all whole slices inside the message
+// (the host checks it: no ragged chunk, no tail, no trip past the chunk).  Each measured 1-5 %
+// faster than the run-time branches.
+template <int DT, int GT, int U, bool DATA, bool FOLD, bool ONE, bool FULL>
 __global__ __launch_bounds__(kThreads) void fused_kernel(RankPtrs bufs, Shape s) {
     u32 r_n, c, w;
     locate(s, blockIdx.x, r_n, c, w);
@@ -406,8 +408,8 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(RankPtrs bufs, Shape s)
         const u32 slice = w + it * s.B_s;
         const u64 first = static_cast<u64>(slice) * (kThreads * U);
         const u32 v0 = static_cast<u32>(first) + threadIdx.x;  // first < 2^31 by construction
-        const bool whole = first + kThreads * U <= whole_vecs;
-        const u32 valid = first < valid_vecs ? valid_vecs : 0u;  // slices past the chunk do nothing
+        const bool whole = FULL || first + kThreads * U <= whole_vecs;
+        const u32 valid = FULL ? s.chunk_vecs : (first < valid_vecs ? valid_vecs : 0u);  // slices past the chunk do nothing
         const u32 ticket = base + it + 1u;
         // Where the slice lives in a partial buffer.  With one or two trips every slice has its
         // own place.  With three or more, a workgroup alternates between two places of its own
@@ -534,7 +536,7 @@ __device__ __forceinline__ void load_slice_packed(const Shape &s, const u64 *buf
     }
 }
 
-template <int DT, int GT, int U, bool FOLD, bool ONE>
+template <int DT, int GT, int U, bool FOLD, bool ONE, bool FULL>
 __global__ __launch_bounds__(kThreads) void fused_packed_kernel(RankPtrs bufs, Shape s) {
     u32 r_n, c, w;
     locate(s, blockIdx.x, r_n, c, w);
@@ -554,8 +556,8 @@ __global__ __launch_bounds__(kThreads) void fused_packed_kernel(RankPtrs bufs, S
         const u32 slice = w + it * s.B_s;
         const u64 first = static_cast<u64>(slice) * (kThreads * U);
         const u32 v0 = static_cast<u32>(first) + threadIdx.x;
-        const bool whole = first + kThreads * U <= whole_vecs;
-        const u32 valid = first < valid_vecs ? valid_vecs : 0u;
+        const bool whole = FULL || first + kThreads * U <= whole_vecs;
+        const u32 valid = FULL ? s.chunk_vecs : (first < valid_vecs ? valid_vecs : 0u);
         // the number of the previous call, from this thread's own first word of the slice (a
         // thread without a word in this slice neither writes nor waits)
         u32 seq = 0u;
@@ -731,71 +733,78 @@ static Shape make_shape(const rar_plan_t &plan, const Tuning &t) {
 
 typedef void (*FusedFn)(RankPtrs, Shape);
 
-// Which instance serves a launch.  The hand-over for N that is not a power of two exists for
-// run-time G and any number of trips only: such plans (outside the paper) take the generic one.
+// Which instance serves a launch.  The special cases (single trip, all slices whole) exist for
+// G = 1, 2, 4, 8 and power-of-two N; run-time G and the hand-over for other N take the generic one.
 struct Variant {
     int dtype, G, unroll;
     bool data;   // false: the barrier-only kernel (no data movement)
     bool fold;   // N is not a power of two
     bool one;    // every workgroup makes a single trip
+    bool full;   // every slice of the launch is a whole slice inside the message
 };
 
-template <int DT, int GT, bool DATA, bool FOLD, bool ONE>
+template <int DT, int GT, bool DATA, bool FOLD, bool ONE, bool FULL>
 static FusedFn pick_unroll(int unroll) {
     switch (unroll) {
-        case 1: return fused_kernel<DT, GT, 1, DATA, FOLD, ONE>;
-        case 2: return fused_kernel<DT, GT, 2, DATA, FOLD, ONE>;
-        case 4: return fused_kernel<DT, GT, 4, DATA, FOLD, ONE>;
-        default: return fused_kernel<DT, GT, 8, DATA, FOLD, ONE>;
+        case 1: return fused_kernel<DT, GT, 1, DATA, FOLD, ONE, FULL>;
+        case 2: return fused_kernel<DT, GT, 2, DATA, FOLD, ONE, FULL>;
+        case 4: return fused_kernel<DT, GT, 4, DATA, FOLD, ONE, FULL>;
+        default: return fused_kernel<DT, GT, 8, DATA, FOLD, ONE, FULL>;
     }
 }
-template <int DT, bool DATA, bool ONE>
+template <int DT, bool DATA, bool ONE, bool FULL>
 static FusedFn pick_group(int G, int unroll) {
     switch (G) {
-        case 1: return pick_unroll<DT, 1, DATA, false, ONE>(unroll);
-        case 2: return pick_unroll<DT, 2, DATA, false, ONE>(unroll);
-        case 4: return pick_unroll<DT, 4, DATA, false, ONE>(unroll);
-        case 8: return pick_unroll<DT, 8, DATA, false, ONE>(unroll);
-        default: return pick_unroll<DT, 0, DATA, false, ONE>(unroll);
-    }
-}
-template <int DT, bool DATA>
-static FusedFn pick_trips(const Variant &v) {
-    if (v.fold) return pick_unroll<DT, 0, DATA, true, false>(v.unroll);
-    // the barrier-only kernel is a measurement aid: one generic instance is enough
-    return v.one && DATA ? pick_group<DT, DATA, true>(v.G, v.unroll) : pick_group<DT, DATA, false>(v.G, v.unroll);
-}
-static FusedFn pick_fused(const Variant &v) {
-    if (v.dtype == RAR_BF16) return v.data ? pick_trips<RAR_BF16, true>(v) : pick_trips<RAR_BF16, false>(v);
-    return v.data ? pick_trips<RAR_F32, true>(v) : pick_trips<RAR_F32, false>(v);
-}
-
-template <int DT, int GT, bool FOLD, bool ONE>
-static FusedFn pick_packed_unroll(int unroll) {
-    switch (unroll) {
-        case 1: return fused_packed_kernel<DT, GT, 1, FOLD, ONE>;
-        case 2: return fused_packed_kernel<DT, GT, 2, FOLD, ONE>;
-        case 4: return fused_packed_kernel<DT, GT, 4, FOLD, ONE>;
-        default: return fused_packed_kernel<DT, GT, 8, FOLD, ONE>;
-    }
-}
-template <int DT, bool ONE>
-static FusedFn pick_packed_group(int G, int unroll) {
-    switch (G) {
-        case 1: return pick_packed_unroll<DT, 1, false, ONE>(unroll);
-        case 2: return pick_packed_unroll<DT, 2, false, ONE>(unroll);
-        case 4: return pick_packed_unroll<DT, 4, false, ONE>(unroll);
-        case 8: return pick_packed_unroll<DT, 8, false, ONE>(unroll);
-        default: return pick_packed_unroll<DT, 0, false, ONE>(unroll);
+        case 1: return pick_unroll<DT, 1, DATA, false, ONE, FULL>(unroll);
+        case 2: return pick_unroll<DT, 2, DATA, false, ONE, FULL>(unroll);
+        case 4: return pick_unroll<DT, 4, DATA, false, ONE, FULL>(unroll);
+        case 8: return pick_unroll<DT, 8, DATA, false, ONE, FULL>(unroll);
+        default: return pick_unroll<DT, 0, DATA, false, false, false>(unroll);
     }
 }
 template <int DT>
-static FusedFn pick_packed_trips(const Variant &v) {
-    if (v.fold) return pick_packed_unroll<DT, 0, true, false>(v.unroll);
-    return v.one ? pick_packed_group<DT, true>(v.G, v.unroll) : pick_packed_group<DT, false>(v.G, v.unroll);
+static FusedFn pick_special(const Variant &v) {
+    if (v.fold) return pick_unroll<DT, 0, true, true, false, false>(v.unroll);
+    if (v.one) return v.full ? pick_group<DT, true, true, true>(v.G, v.unroll) : pick_group<DT, true, true, false>(v.G, v.unroll);
+    return v.full ? pick_group<DT, true, false, true>(v.G, v.unroll) : pick_group<DT, true, false, false>(v.G, v.unroll);
+}
+template <int DT>
+static FusedFn pick_barrier_only(const Variant &v) {  // a measurement aid: the generic instances are enough
+    if (v.fold) return pick_unroll<DT, 0, false, true, false, false>(v.unroll);
+    return pick_group<DT, false, false, false>(v.G, v.unroll);
+}
+static FusedFn pick_fused(const Variant &v) {
+    if (v.dtype == RAR_BF16) return v.data ? pick_special<RAR_BF16>(v) : pick_barrier_only<RAR_BF16>(v);
+    return v.data ? pick_special<RAR_F32>(v) : pick_barrier_only<RAR_F32>(v);
+}
+
+template <int DT, int GT, bool FOLD, bool ONE, bool FULL>
+static FusedFn pick_packed_unroll(int unroll) {
+    switch (unroll) {
+        case 1: return fused_packed_kernel<DT, GT, 1, FOLD, ONE, FULL>;
+        case 2: return fused_packed_kernel<DT, GT, 2, FOLD, ONE, FULL>;
+        case 4: return fused_packed_kernel<DT, GT, 4, FOLD, ONE, FULL>;
+        default: return fused_packed_kernel<DT, GT, 8, FOLD, ONE, FULL>;
+    }
+}
+template <int DT, bool ONE, bool FULL>
+static FusedFn pick_packed_group(int G, int unroll) {
+    switch (G) {
+        case 1: return pick_packed_unroll<DT, 1, false, ONE, FULL>(unroll);
+        case 2: return pick_packed_unroll<DT, 2, false, ONE, FULL>(unroll);
+        case 4: return pick_packed_unroll<DT, 4, false, ONE, FULL>(unroll);
+        case 8: return pick_packed_unroll<DT, 8, false, ONE, FULL>(unroll);
+        default: return pick_packed_unroll<DT, 0, false, false, false>(unroll);
+    }
+}
+template <int DT>
+static FusedFn pick_packed_special(const Variant &v) {
+    if (v.fold) return pick_packed_unroll<DT, 0, true, false, false>(v.unroll);
+    if (v.one) return v.full ? pick_packed_group<DT, true, true>(v.G, v.unroll) : pick_packed_group<DT, true, false>(v.G, v.unroll);
+    return v.full ? pick_packed_group<DT, false, true>(v.G, v.unroll) : pick_packed_group<DT, false, false>(v.G, v.unroll);
 }
 static FusedFn pick_packed(const Variant &v) {
-    return v.dtype == RAR_BF16 ? pick_packed_trips<RAR_BF16>(v) : pick_packed_trips<RAR_F32>(v);
+    return v.dtype == RAR_BF16 ? pick_packed_special<RAR_BF16>(v) : pick_packed_special<RAR_F32>(v);
 }
 
 // The most recent failing HIP status seen by the library on this thread (for rar_last_hip_error).
@@ -829,17 +838,17 @@ int fused_max_resident(int dtype, int G, int unroll, bool packed, bool fold, lon
     DeviceInfo info;
     int rc = device_info(&info);
     if (rc != RAR_OK) return rc;
-    // the smaller of the single-trip and the many-trip instance: the planner asks before it knows
-    // how many trips a launch will make
+    // the smallest over the special-case instances: the planner asks before it knows how many trips
+    // a launch will make
     int fewest = 0;
-    for (int one = 0; one < 2; ++one) {
-        const Variant v{dtype, G, unroll, true, fold, one != 0};
+    for (int k = 0; k < 4; ++k) {
+        const Variant v{dtype, G, unroll, true, fold, (k & 1) != 0, (k & 2) != 0};
         FusedFn fn = packed ? pick_packed(v) : pick_fused(v);
         int per_cu = 0;
         if (note_hip(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(fn), kThreads, 0)) !=
                 hipSuccess || per_cu < 1)
             return RAR_ERR_HIP;
-        if (one == 0 || per_cu < fewest) fewest = per_cu;
+        if (k == 0 || per_cu < fewest) fewest = per_cu;
     }
     *out = static_cast<long>(fewest) * info.compute_units;
     return RAR_OK;
@@ -860,12 +869,20 @@ int launch_fill_zero(void *words, size_t bytes, hipStream_t stream) {
     return check_launch();
 }
 
+// Every slice of every workgroup is a whole slice inside the message: no tail, no ragged or short
+// chunk, no trip past the end of a chunk.
+static bool all_slices_whole(const Geometry &g, const Tuning &t) {
+    const size_t slice = static_cast<size_t>(kThreads) * t.unroll;
+    return g.n % g.per_vec == 0 && g.n == static_cast<size_t>(g.G) * g.chunk_len && g.chunk_vecs % slice == 0 &&
+           static_cast<size_t>(t.B_s) * t.iters * slice == g.chunk_vecs;
+}
+
 int launch_fused(const rar_plan_t &plan, const RankPtrs &bufs, const Tuning &t, bool data, hipStream_t stream) {
     begin_launch();
     const Geometry &g = plan.geo;
     const Shape s = make_shape(plan, t);
     const u32 grid = static_cast<u32>(g.P) * t.B_s;
-    FusedFn fn = pick_fused(Variant{g.dtype, g.G, t.unroll, data, g.fold != 0, t.iters == 1});
+    FusedFn fn = pick_fused(Variant{g.dtype, g.G, t.unroll, data, g.fold != 0, t.iters == 1, all_slices_whole(g, t)});
     fn<<<dim3(grid), dim3(kThreads), 0, stream>>>(bufs, s);
     return check_launch();
 }
@@ -875,7 +892,7 @@ int launch_fused_packed(const rar_plan_t &plan, const RankPtrs &bufs, const Tuni
     const Geometry &g = plan.geo;
     const Shape s = make_shape(plan, t);
     const u32 grid = static_cast<u32>(g.P) * t.B_s;
-    FusedFn fn = pick_packed(Variant{g.dtype, g.G, t.unroll, true, g.fold != 0, t.iters == 1});
+    FusedFn fn = pick_packed(Variant{g.dtype, g.G, t.unroll, true, g.fold != 0, t.iters == 1, all_slices_whole(g, t)});
     fn<<<dim3(grid), dim3(kThreads), 0, stream>>>(bufs, s);
     return check_launch();
 }
