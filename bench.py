@@ -29,6 +29,19 @@ def algorithmic_bytes(P: int, G: int, N: int, msg_bytes: int) -> int:
     return P * (2 * msg_bytes + (3 * L + 2) * msg_bytes // G)
 
 
+def moved_bytes(P: int, G: int, N: int, msg_bytes: int) -> int:
+    """Bytes the fused kernel has to move for one all-reduce (N a power of two): per rank it reads
+    the G local messages' chunk (M) and one peer partial per step (L * M/G), and writes its own
+    partial for every step but the last (L * M/G: S_0 .. S_{L-1}) and the gathered result (M):
+    2M + 2L * M/G.  A rank's own partial stays in registers from step to step and the last
+    partial is never written out, which is what separates this from the schedule's count above."""
+    L = N.bit_length() - 1
+    return P * (2 * msg_bytes + 2 * L * msg_bytes // G)
+
+
+MIN_CALLS_SHORT = 300   # kernels of a few microseconds are timed over at least this many calls
+
+
 def device_bufs(x):
     """x[P, n] on the host -> P rank buffers on the device, as the rows of ONE allocation.
     (The library takes any P pointers; rows of a single allocation measured 10-15 % faster than
@@ -125,6 +138,55 @@ def copy_probe(times: int = 3) -> None:
     torch.cuda.synchronize()
 
 
+def streaming_ceilings():
+    """What plain streaming kernels reach on this device, beyond the 256 MiB memory-side cache: a
+    read-only pass over 1 GiB and a copy of 512 MiB (bytes counted = read + written)."""
+    import torch
+    import paper_2511_09557_amd as rar
+    st = torch.cuda.current_stream().cuda_stream
+    big = torch.full((1 << 30,), 5, dtype=torch.uint8, device="cuda:0")
+    sink = torch.zeros(16, dtype=torch.uint8, device="cuda:0")
+    half = 512 << 20
+    _, ev = time_calls(lambda: rar.rar_read_probe(sink.data_ptr(), big.data_ptr(), 1 << 30, st), 3, 20)
+    read = (1 << 30) / (ev / 20 * 1e-3) / 1e9
+    _, ev = time_calls(lambda: rar.rar_copy_probe(big.data_ptr() + half, big.data_ptr(), half, st), 3, 20)
+    copy = 2 * half / (ev / 20 * 1e-3) / 1e9
+    del big
+    torch.cuda.empty_cache()
+    return {"read_only_GBps": read, "copy_GBps": copy,
+            "note": "library probes rar_read_probe (1 GiB) and rar_copy_probe (512 MiB -> 512 MiB), 16-byte vectors, 20 calls each"}
+
+
+def cold_leg(ar, stream_calls: int = 20, replays: int = 5):
+    """The bound all-reduce with the memory-side cache swept before every call: HIP graphs of
+    `stream_calls` x (256 MiB copy, all-reduce) against graphs of the copies alone; the difference
+    is the all-reduce on cold caches.  Returns microseconds per call."""
+    import torch
+    import paper_2511_09557_amd as rar
+    src = torch.full((COPY_PROBE_BYTES,), 3, dtype=torch.uint8, device="cuda:0")
+    dst = torch.empty_like(src)
+
+    def sweep_caches(st):
+        rar.rar_copy_probe(dst.data_ptr(), src.data_ptr(), COPY_PROBE_BYTES, st.cuda_stream)
+
+    def both(st):
+        sweep_caches(st)
+        ar.launch(st)
+    alone = min(time_graph(sweep_caches, stream_calls, 1, replays) for _ in range(2))
+    pair = min(time_graph(both, stream_calls, 1, replays) for _ in range(2))
+    del src, dst
+    return pair - alone, alone
+
+
+def bench_chain(ar, K: int = 100, launches: int = 10):
+    """Microseconds per all-reduce when K of them run in ONE persistent launch (rar_allreduce_chain)."""
+    import torch
+    cur = torch.cuda.current_stream().cuda_stream
+    ar.launch_chain(2, cur)
+    _, ev = time_calls(lambda: ar.launch_chain(K, cur), 2, launches)
+    return ev * 1000.0 / (launches * K)
+
+
 def bench_step_combine(warmup: int, steps: int):
     """rar_step_combine (one rank's exchange-and-sum, 3 * n * 2 bytes of traffic) on c4's per-step
     message (512 KiB, launch-bound) and on 128 MiB (bandwidth-bound; beyond the memory-side cache)."""
@@ -154,7 +216,10 @@ def measured_traffic(workload: str):
         return None
 
 
-def bench_workload(name: str, warmup: int, steps: int, extras: bool, mode: str = "fused"):
+def bench_workload(name: str, warmup: int, steps: int, extras: bool, mode: str = "fused", headline: bool = True):
+    """One workload.  The headline workload's fused call is timed over exactly `steps` calls after
+    `warmup` (the figure of the JSON line); every other figure uses its own number of calls, at
+    least MIN_CALLS_SHORT for kernels of a few microseconds, so that no figure is a 10-call sample."""
     import torch
     import paper_2511_09557_amd as rar
     import rar_inputs as ri
@@ -162,30 +227,38 @@ def bench_workload(name: str, warmup: int, steps: int, extras: bool, mode: str =
     x = ri.make_inputs(w)
     dtype = rar.RAR_BF16 if w.dtype == "bf16" else rar.RAR_F32
     out = {"P": w.P, "G": w.G, "N": w.N, "bytes_per_rank": w.bytes_per_rank,
-           "algorithmic_bytes": algorithmic_bytes(w.P, w.G, w.N, w.bytes_per_rank)}
+           "algorithmic_bytes": algorithmic_bytes(w.P, w.G, w.N, w.bytes_per_rank),
+           "moved_bytes": moved_bytes(w.P, w.G, w.N, w.bytes_per_rank)}
     bufs = device_bufs(x)
     ar = rar.AllReduce(w.P, w.G, w.n, dtype, rar.RAR_MODE_FUSED)
     if mode != "fused":     # only with --no-extras: the headline call in another mode (for per-kernel profiles)
         ar.set_mode({"stepwise": rar.RAR_MODE_STEPWISE, "packed": rar.RAR_MODE_FUSED_PACKED, "auto": rar.RAR_MODE_AUTO}[mode])
     ar.bind(bufs)
     cur = torch.cuda.current_stream().cuda_stream   # looked up once: the timed calls pass the handle
-    wall, ev_ms = time_calls(lambda: ar.launch(cur), warmup, steps)
+    short = w.bytes_per_rank <= (1 << 20)           # c1-c3: a few microseconds per call
+    calls = steps if headline else max(steps, MIN_CALLS_SHORT if short else 100)
+    warm = warmup if headline else max(warmup, 50)
+    sub_calls = max(steps, MIN_CALLS_SHORT) if short else max(min(steps, 500), 100)   # for the side measurements
+    wall, ev_ms = time_calls(lambda: ar.launch(cur), warm, calls)
     assert ar.status() == 0
-    out["fused_us"] = ev_ms * 1000.0 / steps
-    out["fused_wall_us"] = wall * 1e6 / steps
+    out["fused_us"] = ev_ms * 1000.0 / calls
+    out["fused_wall_us"] = wall * 1e6 / calls
+    out["fused_calls_timed"] = calls
     if extras:  # two more repetitions of the same timed region, to show the spread
-        reps = [out["fused_us"]] + [time_calls(lambda: ar.launch(cur), 10, steps)[1] * 1000.0 / steps for _ in range(2)]
+        reps = [out["fused_us"]] + [time_calls(lambda: ar.launch(cur), 10, calls)[1] * 1000.0 / calls for _ in range(2)]
         out["fused_us_repetitions"] = reps
     out["tuning"] = dict(zip(("B_s", "C_s"), ar.tuning()))
     if extras:
+        out["side_calls_timed"] = sub_calls
         ar.set_mode(rar.RAR_MODE_STEPWISE)
-        _, ev = time_calls(lambda: ar.launch(cur), warmup // 4 + 1, max(steps // 4, 10))
-        out["stepwise_us"] = ev * 1000.0 / max(steps // 4, 10)
+        k = max(sub_calls // 3, 100)
+        _, ev = time_calls(lambda: ar.launch(cur), 20, k)
+        out["stepwise_us"] = ev * 1000.0 / k
         ar.set_mode(rar.RAR_MODE_FUSED)
-        _, ev = time_calls(lambda: ar.launch_floor(cur), warmup, steps)
-        out["launch_floor_us"] = ev * 1000.0 / steps
-        _, ev = time_calls(lambda: ar.barrier_only(cur), warmup, steps)
-        out["barrier_only_us"] = ev * 1000.0 / steps
+        _, ev = time_calls(lambda: ar.launch_floor(cur), 50, sub_calls)
+        out["launch_floor_us"] = ev * 1000.0 / sub_calls
+        _, ev = time_calls(lambda: ar.barrier_only(cur), 50, sub_calls)
+        out["barrier_only_us"] = ev * 1000.0 / sub_calls
         # the same three things inside HIP graphs of 100 calls: the device-side cost without
         # the host's launch rate.  floor = launch only; barrier = flags only; fused = everything
         out["graph100_us"] = time_graph(lambda st: ar.launch(st), 100, 2, 10)
@@ -194,6 +267,13 @@ def bench_workload(name: str, warmup: int, steps: int, extras: bool, mode: str =
         ar.set_mode(rar.RAR_MODE_STEPWISE)
         out["graph100_stepwise_us"] = time_graph(lambda st: ar.launch(st), 100, 2, 10)
         ar.set_mode(rar.RAR_MODE_FUSED)
+        # 100 all-reduces in ONE persistent launch (rar_allreduce_chain): a workgroup starts call
+        # k+1 as soon as its own slices of call k are gathered; per-call time
+        out["chain100_us"] = bench_chain(ar)
+        # the memory-side cache swept before every call (256 MiB copy in between, copy time subtracted)
+        cold, sweep_us = cold_leg(ar)
+        out["cold_us"] = cold
+        out["cold_sweep_copy_us"] = sweep_us
         # back-to-back calls versus calls with compute in between (the paper's Appendix B runs a
         # synthetic matmul between all-reduces).  The compute here is what precedes the all-reduce
         # in a tensor-parallel layer: every rank's row-parallel product, tokens x hidden/P @
@@ -221,11 +301,12 @@ def bench_workload(name: str, warmup: int, steps: int, extras: bool, mode: str =
         try:
             ar.set_mode(rar.RAR_MODE_FUSED_PACKED)
         except rar.RarError:
-            out["packed_us"] = out["graph100_packed_us"] = None
+            out["packed_us"] = out["graph100_packed_us"] = out["chain100_packed_us"] = None
         else:
-            _, ev = time_calls(lambda: ar.launch(cur), warmup, steps)
-            out["packed_us"] = ev * 1000.0 / steps
+            _, ev = time_calls(lambda: ar.launch(cur), 50, sub_calls)
+            out["packed_us"] = ev * 1000.0 / sub_calls
             out["graph100_packed_us"] = time_graph(lambda st: ar.launch(st), 100, 2, 10)
+            out["chain100_packed_us"] = bench_chain(ar)
             out["packed_tuning"] = dict(zip(("B_s", "C_s"), ar.tuning()))
             ar.set_mode(rar.RAR_MODE_FUSED)
         # two independent chains of calls side by side (two plans, two sets of buffers, two streams
@@ -242,13 +323,14 @@ def bench_workload(name: str, warmup: int, steps: int, extras: bool, mode: str =
         ar_b.close()
         del bufs_b
         rar.rar_plan_set_concurrency(ar.plan, 1)
-        ar.set_mode(rar.RAR_MODE_FUSED)
-        # what a caller who sets nothing gets (the library's automatic choice between the two)
-        ar.set_mode(rar.RAR_MODE_AUTO)
+        # what a caller who sets nothing gets (the library's automatic choice between the two),
+        # timed on its own, eagerly and in graphs
         packed = ar.effective_mode() == rar.RAR_MODE_FUSED_PACKED
         out["auto_mode"] = "fused_packed" if packed else "fused"
-        out["auto_us"] = out["packed_us"] if packed else out["fused_us"]
-        out["graph100_auto_us"] = out["graph100_packed_us"] if packed else out["graph100_us"]
+        _, ev = time_calls(lambda: ar.launch(cur), 50, sub_calls)
+        out["auto_us"] = ev * 1000.0 / sub_calls
+        out["graph100_auto_us"] = time_graph(lambda st: ar.launch(st), 100, 2, 10)
+        out["chain100_auto_us"] = bench_chain(ar)
         ar.set_mode(rar.RAR_MODE_FUSED)
         assert ar.status() == 0
     ar.close()
@@ -462,6 +544,82 @@ def cpu_baseline(name: str):
                               "sample": f"{single_reps} whole all-reduces of the same workload"}}
 
 
+def tuning_scan(path: str) -> None:
+    """Every (B_s, C_s) the planner can launch against its built-in choice, over P = 8..128,
+    G = 1..8, 16 KiB .. 16 MiB, bf16 and fp32, inside HIP graphs of 20 calls.  Writes a markdown
+    summary (the built-in choice's distance from the best pair of each shape)."""
+    import torch
+    import paper_2511_09557_amd as rar
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(SWEEP_SEED + 5)
+    rows = []
+    for dt, code, es, tdt in (("bf16", rar.RAR_BF16, 2, torch.bfloat16), ("f32", rar.RAR_F32, 4, torch.float32)):
+        for P, G in ((8, 4), (16, 4), (32, 4), (64, 4), (128, 4), (64, 8), (16, 8), (8, 1), (32, 2)):
+            for lg in range(14, 25):
+                nbytes = 1 << lg
+                n = nbytes // es
+                whole = torch.randn(P, n, device="cuda:0", generator=gen).to(tdt)
+                ar = rar.AllReduce(P, G, n, code, rar.RAR_MODE_FUSED)
+                ar.bind([whole[p] for p in range(P)])
+                ar.launch()
+                torch.cuda.synchronize()
+                default = ar.tuning()
+                reps = 10 if nbytes <= (1 << 22) else 3
+                res = {}
+                for C_s in (4096, 8192, 16384, 32768):
+                    for div in (1, 2):
+                        ar.set_tuning(0, C_s)
+                        B = max(1, ar.tuning()[0] // div)      # the widest grid the planner allows, and half of it
+                        ar.set_tuning(B, C_s)
+                        t = ar.tuning()
+                        if t in res:
+                            continue
+                        res[t] = time_graph(lambda st: ar.launch(st), 20, 1, reps)
+                        assert ar.status() == 0, (t, P, G, nbytes, dt)
+                ar.set_tuning(0, 0)
+                d = res.get(default) or time_graph(lambda st: ar.launch(st), 20, 1, reps)
+                best = min(res, key=res.get)
+                rows.append((dt, P, G, nbytes, default, d, best, res[best]))
+                print(f"{dt} P={P} G={G} {nbytes} default {default} {d:.2f} best {best} {res[best]:.2f}", file=sys.stderr, flush=True)
+                ar.close()
+                del whole
+    ratios = [r[5] / r[7] for r in rows]
+    geo = 1.0
+    for r in ratios:
+        geo *= r ** (1.0 / len(ratios))
+    worst = max(rows, key=lambda r: r[5] / r[7])
+    with open(path, "w") as f:
+        f.write("# Built-in (B_s, C_s) against the best of the scanned pairs, one MI355X\n\n"
+                "command: `python3 bench.py --tuning-scan <this file>`; fused mode (flag exchange), microseconds per all-reduce\n"
+                "inside HIP graphs of 20 calls; candidates: C_s in {4, 8, 16, 32} KiB x B_s in {widest grid the planner\n"
+                "allows (four workgroups per compute unit at most), half of it}.\n\n"
+                f"shapes: {len(rows)}; built-in / best: mean {sum(ratios) / len(ratios):.3f}, geometric mean {geo:.3f}, "
+                f"worst {worst[5] / worst[7]:.3f} ({worst[0]} P={worst[1]} G={worst[2]} {worst[3]} B)\n\n"
+                "| type | P | G | bytes per rank | built-in (B_s, C_s) | us | best (B_s, C_s) | us | ratio |\n|---|---|---|---|---|---|---|---|---|\n")
+        for dt, P, G, nbytes, default, d, best, b in rows:
+            f.write(f"| {dt} | {P} | {G} | {nbytes} | {default} | {d:.2f} | {best} | {b:.2f} | {d / b:.3f} |\n")
+
+
+def cold_loop(workload: str, calls: int) -> None:
+    """For a profiler: `calls` x (256 MiB copy, fused all-reduce of the workload) launched eagerly, so
+    that a kernel trace shows the all-reduce kernel's own duration on cold caches."""
+    import torch
+    import paper_2511_09557_amd as rar
+    import rar_inputs as ri
+    w = ri.WORKLOADS[workload]
+    bufs = device_bufs(ri.make_inputs(w))
+    ar = rar.AllReduce(w.P, w.G, w.n, rar.RAR_BF16, rar.RAR_MODE_FUSED)
+    ar.bind(bufs)
+    src = torch.full((COPY_PROBE_BYTES,), 3, dtype=torch.uint8, device="cuda:0")
+    dst = torch.empty_like(src)
+    st = torch.cuda.current_stream().cuda_stream
+    for _ in range(calls):
+        rar.rar_copy_probe(dst.data_ptr(), src.data_ptr(), COPY_PROBE_BYTES, st)
+        ar.launch(st)
+    assert ar.status() == 0
+    ar.close()
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -472,9 +630,11 @@ def main() -> int:
     ap.add_argument("--mode", default="fused", choices=["fused", "stepwise", "packed", "auto"],
                     help="with --no-extras: run the headline workload in this mode (the JSON line says which)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--cold-loop", type=int, metavar="CALLS", help="for a profiler: only CALLS x (cache sweep, fused all-reduce of --workload)")
     ap.add_argument("--sensitivity", metavar="OUT.md", help="run the B_s x C_s sensitivity study instead and write it to this file")
     ap.add_argument("--hierarchy", metavar="OUT.md", help="run the flat-versus-hierarchical study instead and write it to this file")
     ap.add_argument("--sweep", metavar="OUT.jsonl", help="run the message-size sweep instead and write it to this file")
+    ap.add_argument("--tuning-scan", metavar="OUT.md", help="run the scan of all (B_s, C_s) against the built-in choice instead")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build emulates all P ranks on ONE GPU; --gpus must be 1 "
@@ -494,6 +654,13 @@ def main() -> int:
     if args.hierarchy:
         hierarchy(args.hierarchy)
         return 0
+    if args.tuning_scan:
+        tuning_scan(args.tuning_scan)
+        return 0
+    if args.cold_loop:
+        cold_loop(args.workload, args.cold_loop)
+        copy_probe()
+        return 0
 
     if args.mode != "fused" and not args.no_extras:
         print("bench.py: --mode needs --no-extras", file=sys.stderr)
@@ -502,8 +669,30 @@ def main() -> int:
     copy_probe()
     w = ri.WORKLOADS[args.workload]
     us = head["fused_us"]
-    achieved = head["algorithmic_bytes"] / (us * 1e-6) / 1e9
+    # The roofline figure: bytes the kernel has to move (moved_bytes) over its launch duration.
+    # The schedule's own count (every partial materialised: algorithmic_bytes) is reported beside it
+    # as a rate without a fraction: the fused kernel does not move those bytes.
+    moved = head["moved_bytes"] if args.mode in ("fused", "auto") else head["algorithmic_bytes"]
+    achieved = moved / (us * 1e-6) / 1e9
     traffic = measured_traffic(args.workload) if args.mode == "fused" else None
+    roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
+                "kernel": "fused_kernel" if args.mode == "fused" else args.mode,
+                "bytes_per_launch": moved, "bytes_formula": "P*(2M + 2*log2(N)*M/G)" if args.mode in ("fused", "auto") else "P*(2M + (3*log2(N)+2)*M/G)",
+                "avg_launch_us": us,
+                "schedule_bytes_per_launch": head["algorithmic_bytes"],
+                "schedule_GBps": head["algorithmic_bytes"] / (us * 1e-6) / 1e9,
+                # L2 <-> fabric bytes per launch from the committed rocprofv3 --pmc summary (the
+                # memory-side cache can serve part of them, so this is not HBM traffic proper)
+                "traffic_GBps": (traffic / (us * 1e-6) / 1e9) if traffic else None,
+                "traffic_frac": (traffic / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS) if traffic else None}
+    if not args.no_extras:
+        cold = head["cold_us"]
+        roofline["cold"] = {"us": cold, "GBps": moved / (cold * 1e-6) / 1e9, "frac": moved / (cold * 1e-6) / 1e9 / HBM_PEAK_GBPS,
+                            "traffic_GBps": (traffic / (cold * 1e-6) / 1e9) if traffic else None,
+                            "method": "HIP graphs of 20 x (256 MiB copy, all-reduce) minus graphs of the copies alone: "
+                                      "the memory-side cache and the L2s are swept before every call"}
+        roofline["streaming_ceilings"] = streaming_ceilings()
     line = {
         "metric": "us per all-reduce at 128KB-2MB bf16 (P virtual ranks); achieved HBM GB/s vs peak",
         "value": us,
@@ -520,26 +709,18 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": f"{args.workload}: P={w.P} (G={w.G} x N={w.N}), {w.bytes_per_rank} B bf16 per rank, {args.mode} mode",
                    "tuning": head["tuning"]},
-        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
-                     "kernel": "fused_kernel" if args.mode == "fused" else args.mode, "algorithmic_bytes_per_launch": head["algorithmic_bytes"],
-                     "avg_launch_us": us,
-                     # the kernel moves fewer bytes than the schedule's algorithmic count (a rank's own
-                     # partial stays in registers between steps, the last partial is never written out),
-                     # so `frac` can exceed what the memory system itself delivers: that is `traffic_frac`
-                     "traffic_GBps": (traffic / (us * 1e-6) / 1e9) if traffic else None,
-                     "traffic_frac": (traffic / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS) if traffic else None},
+        "roofline": roofline,
     }
     if not args.no_extras:
         detail = {args.workload: head}
         for other in ("c1", "c2", "c3", "c4"):
             if other != args.workload:
-                detail[other] = bench_workload(other, args.warmup, max(args.steps // 2, 10), extras=True)
+                detail[other] = bench_workload(other, args.warmup, args.steps, extras=True, headline=False)
         for k, v in detail.items():
-            v["achieved_GBps"] = v["algorithmic_bytes"] / (v["fused_us"] * 1e-6) / 1e9
-            v["traffic"] = measured_traffic(k)   # HBM bytes per launch from the committed --pmc summaries
+            v["achieved_GBps"] = v["moved_bytes"] / (v["fused_us"] * 1e-6) / 1e9
+            v["traffic"] = measured_traffic(k)   # L2 <-> fabric bytes per launch from the committed --pmc summaries
         line["detail"] = detail
-        line["step_combine"] = bench_step_combine(args.warmup, args.steps)
+        line["step_combine"] = bench_step_combine(min(args.warmup, 50), max(args.steps, MIN_CALLS_SHORT))
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline(args.workload)
     print(json.dumps(line))

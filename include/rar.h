@@ -19,17 +19,26 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls that take
  *     a stream only enqueue work and return; results are valid in stream order.
  *   - Every function returns RAR_OK (0) or a negative rar_status.  No exceptions, no aborts.
- *   - Nothing here allocates or frees device memory; scratch is lent by the caller.
+ *   - Nothing here allocates or frees device memory; scratch is lent by the caller.  A plan's
+ *     first launch allocates one word of pinned host memory (the time-out word below).
  *   - A plan is not thread-safe, and two all-reduces on one plan must not overlap in time
  *     (they share the plan's scratch): order them on one stream or use two plans.  A plan
  *     belongs to the device that is current at its first launch (it remembers that device's
  *     size and how many workgroups of each kernel it holds at once).
  *   - The fused modes size their grid so that every workgroup is resident at once on an
- *     otherwise idle device (their step barriers spin).  Other work on other streams may run at
- *     the same time as long as it finishes by itself; several fused all-reduces at the same
- *     time need rar_plan_set_concurrency.  All waits are bounded (rar_plan_set_wait_limit_us):
- *     a call that cannot proceed ends with RAR_ERR_TIMEOUT instead of hanging.
- *     RAR_MODE_STEPWISE has no such requirement.
+ *     otherwise idle device (their step barriers spin): never more than four workgroups per
+ *     compute unit, and never more than the device holds of the kernel in question.  Other
+ *     work on other streams may run at the same time as long as it finishes by itself.  Fused
+ *     all-reduces of different plans on different streams are, by default, ordered one after
+ *     the other by the library (an event between the two streams); rar_plan_set_concurrency
+ *     lets them overlap.  RAR_MODE_STEPWISE has no residency requirement.
+ *   - All waits are bounded (rar_plan_set_wait_limit_us): a call that cannot proceed ends
+ *     instead of hanging, its output is then unspecified, and the plan is "poisoned": every
+ *     later launch on it returns RAR_ERR_TIMEOUT without enqueuing anything until
+ *     rar_plan_status has been called (which reports the time-out and re-arms the plan).
+ *   - Stream capture: a plan's first launch, and the first after a time-out, must be made
+ *     outside capture (they set up flags and host memory); inside capture they return
+ *     RAR_ERR_CAPTURE.  Every later launch may be captured and replayed.
  */
 #ifndef RAR_H
 #define RAR_H
@@ -68,7 +77,9 @@ typedef enum rar_status {
     RAR_ERR_ALIGN = -6,   /* a data pointer is not 16-byte aligned                          */
     RAR_ERR_HIP = -7,     /* a HIP call failed (no device, launch error, ...)               */
     RAR_ERR_TIMEOUT = -8, /* a step barrier gave up waiting (reported by rar_plan_status)   */
-    RAR_ERR_TUNING = -9   /* rar_plan_set_tuning: unsupported B_s / C_s                     */
+    RAR_ERR_TUNING = -9,  /* rar_plan_set_tuning: unsupported B_s / C_s                     */
+    RAR_ERR_CAPTURE = -10 /* a plan's first launch (or the first after a time-out) was made
+                             while its stream was being captured                            */
 } rar_status;
 
 #define RAR_MAX_RANKS 128
@@ -124,7 +135,8 @@ int rar_plan_chunk(const rar_plan_t *plan, int c, size_t *offset, size_t *length
 /* Bytes of device scratch rar_allreduce needs: a 256-byte header (status word), the step
  * barrier flags, the per-step partial buffers S_0..S_L of every rank
  * (Section 4.2.1: one buffer per inter-node step, so a rank may run ahead of its peer) and,
- * for chunks of at most 256 KiB, the per-step data+flag buffers of the packed mode. */
+ * for chunks of at most 256 KiB, the per-step data+flag buffers of the packed mode plus a
+ * second set of both kinds of buffers for the odd calls of rar_allreduce_chain. */
 size_t rar_plan_scratch_bytes(const rar_plan_t *plan);
 
 /* Where things live inside the scratch, as byte offsets and sizes (host pointers, each may be
@@ -154,16 +166,23 @@ int rar_plan_effective_mode(const rar_plan_t *plan);
  * per trip (its "chunk" of the chunked pipeline).  C_s must be 4096, 8192, 16384 or 32768;
  * 1 <= B_s <= 256.  B_s = 0 and/or C_s = 0 restore the built-in choice for that parameter.
  * They change timing only, never a result bit.  In fused mode B_s is clamped at launch so
- * that all P*B_s workgroups are resident at once (the step barriers need that). */
+ * that all P*B_s workgroups are resident at once (the step barriers need that): at most four
+ * workgroups per compute unit of the device, fewer if the kernel in question fits fewer. */
 int rar_plan_set_tuning(rar_plan_t *plan, int B_s, size_t C_s);
 int rar_plan_get_tuning(const rar_plan_t *plan, int *B_s, size_t *C_s);
 
 /* How many fused all-reduces (of different plans, on different streams) the caller lets run on
- * the device at the same time: 1 (default) to 8.  The built-in B_s and the residency clamp then
- * leave each plan 1/k of the device.  Two fused kernels that together exceed what the device
- * holds can each keep workgroup slots the other one waits for; the waits are bounded, so such
- * calls end in RAR_ERR_TIMEOUT rather than hang, but they do not complete.  Kernels that do not
- * wait for anything (matrix products, copies) may share the device freely. */
+ * the device at the same time: 1 (default) to 8.
+ * k = 1: the library keeps fused launches apart.  A fused launch on another stream than the
+ *   library's previous fused launch on the device first waits (hipStreamWaitEvent) for an event
+ *   recorded on that previous stream, so the two kernels never share the device.  (Two fused
+ *   kernels that together exceed what the device holds can each keep workgroup slots the other
+ *   one waits for; the waits are bounded, so such calls would end in RAR_ERR_TIMEOUT rather than
+ *   hang, but they would not complete.)  Inside stream capture the dependency is added only if
+ *   both streams belong to the same capture; graphs replayed side by side are the caller's to order.
+ * k > 1: no such ordering; the built-in B_s and the residency clamp leave the plan 1/k of the
+ *   device, so that k such kernels fit at once.
+ * Kernels that do not wait for anything (matrix products, copies) may share the device freely. */
 int rar_plan_set_concurrency(rar_plan_t *plan, int k);
 
 /* Upper bound on the time one step-barrier wait may take before the kernel gives up, in
@@ -172,8 +191,9 @@ int rar_plan_set_concurrency(rar_plan_t *plan, int k);
  * output buffers are then unspecified. */
 int rar_plan_set_wait_limit_us(rar_plan_t *plan, uint64_t microseconds);
 
-/* Synchronise `stream`, read the status word of the scratch header and return it
- * (RAR_OK or RAR_ERR_TIMEOUT), clearing it and scheduling a flag reset if it was set. */
+/* Synchronise `stream`, then report whether a step-barrier wait of this plan has given up since
+ * the last report: RAR_OK or RAR_ERR_TIMEOUT.  After a time-out the plan is re-armed: the next
+ * launch (which must be outside stream capture) clears the flags first. */
 int rar_plan_status(rar_plan_t *plan, void *stream);
 
 /* ---- one rank's exchange-and-sum (Algorithm 1, RD_inter: B_send[l+1] <- dst + src) --------
@@ -198,6 +218,20 @@ int rar_step_combine(void *dst, const void *src, size_t chunk, size_t n, int dty
  */
 int rar_allreduce(void *const *bufs, rar_plan_t *plan, void *stream);
 
+/* K all-reduces of the same buffers, each on the result of the one before, in ONE persistent
+ * launch (K >= 1, at most 65536): the same bits as K calls of rar_allreduce.  This is the part
+ * of Algorithm 1 that lets a rank start call k+1 before call k has finished everywhere
+ * (Section 4.2.1, per-step buffers; Section 4.2.3, sequence numbers instead of a barrier
+ * between calls): a workgroup goes on to the next call as soon as its own slices of the current
+ * one are gathered; nothing orders the calls but the step flags (or the sequence numbers in the
+ * exchanged words).  An exchange buffer is written again two calls later; by then its reader is
+ * done with it, because the writer has since waited, in the call in between, for data that the
+ * reader produces only after it finished reading.  That takes two buffers per step and rank:
+ * plans with chunks of at most 256 KiB have a second set in their scratch, longer chunks
+ * alternate between two places inside the first set (B_s is narrowed for that if need be).
+ * Runs the plan's fused mode (flag or data+flag exchange); RAR_MODE_STEPWISE: RAR_ERR_ARG. */
+int rar_allreduce_chain(void *const *bufs, rar_plan_t *plan, int K, void *stream);
+
 /* Pick B_s and C_s by measurement (the paper tunes both once per message size and node count,
  * Section 4.2.1, and leaves heuristics to future work).  Runs the fused all-reduce of the
  * plan's current mode on `bufs` (same contract as rar_allreduce; the buffers are overwritten
@@ -205,7 +239,9 @@ int rar_allreduce(void *const *bufs, rar_plan_t *plan, void *stream);
  * `calls` timed calls each (>= 1) after two warm-up calls, timed with HIP events on `stream`,
  * and leaves the fastest pair set in the plan as if by rar_plan_set_tuning.  Synchronises the
  * stream.  *best_us (host, may be NULL) receives the winner's mean microseconds per call.
- * Stepwise mode has nothing to tune: RAR_ERR_ARG. */
+ * A candidate during which a step-barrier wait gave up is discarded (the plan is re-armed and
+ * the search goes on); RAR_ERR_TIMEOUT if no candidate survives.  Must be called outside stream
+ * capture.  Stepwise mode has nothing to tune: RAR_ERR_ARG. */
 int rar_autotune(void *const *bufs, rar_plan_t *plan, void *stream, int calls, double *best_us);
 
 /* ---- measurement aids (used by the benchmark, no effect on results) -----------------------
@@ -216,10 +252,14 @@ int rar_autotune(void *const *bufs, rar_plan_t *plan, void *stream, int calls, d
  *   barrier traffic (flag stores, waits, fences) of a real call.
  * rar_copy_probe: enqueue a plain 16-byte-vector copy of `bytes` bytes (multiple of 16)
  *   from src to dst (device), the known-size kernel that rocprof counters are scaled by.
+ * rar_read_probe: enqueue a kernel that only reads `bytes` bytes (multiple of 16) at src with
+ *   16-byte loads (the streaming-read rate of the device); *sink (device, 16 bytes) receives a
+ *   value that depends on every vector read.
  */
 int rar_launch_floor(rar_plan_t *plan, void *stream);
 int rar_barrier_only(rar_plan_t *plan, void *stream);
 int rar_copy_probe(void *dst, const void *src, size_t bytes, void *stream);
+int rar_read_probe(void *sink, const void *src, size_t bytes, void *stream);
 
 #ifdef __cplusplus
 }

@@ -62,10 +62,12 @@ def _load() -> ctypes.CDLL:
         "rar_plan_status": (ci, [vp, vp]),
         "rar_step_combine": (ci, [vp, vp, sz, sz, ci, vp]),
         "rar_allreduce": (ci, [ctypes.POINTER(vp), vp, vp]),
+        "rar_allreduce_chain": (ci, [ctypes.POINTER(vp), vp, ci, vp]),
         "rar_autotune": (ci, [ctypes.POINTER(vp), vp, vp, ci, ctypes.POINTER(ctypes.c_double)]),
         "rar_launch_floor": (ci, [vp, vp]),
         "rar_barrier_only": (ci, [vp, vp]),
         "rar_copy_probe": (ci, [vp, vp, sz, vp]),
+        "rar_read_probe": (ci, [vp, vp, sz, vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(L, name)
@@ -79,7 +81,7 @@ EXPORTS = ["rar_version", "rar_strerror", "rar_last_hip_error", "rar_plan", "rar
            "rar_plan_scratch_bytes", "rar_plan_scratch_layout", "rar_plan_set_scratch", "rar_plan_set_mode",
            "rar_plan_get_mode", "rar_plan_effective_mode", "rar_plan_set_tuning", "rar_plan_get_tuning",
            "rar_plan_set_concurrency", "rar_plan_set_wait_limit_us", "rar_plan_status", "rar_step_combine", "rar_allreduce",
-           "rar_autotune", "rar_launch_floor", "rar_barrier_only", "rar_copy_probe"]
+           "rar_allreduce_chain", "rar_autotune", "rar_launch_floor", "rar_barrier_only", "rar_copy_probe", "rar_read_probe"]
 
 
 def _check(status: int, where: str) -> int:
@@ -195,6 +197,11 @@ def rar_allreduce(buf_ptrs: Sequence[int], plan: int, stream: int = 0) -> None:
     _check(lib.rar_allreduce(arr, plan, stream), "rar_allreduce")
 
 
+def rar_allreduce_chain(buf_ptrs: Sequence[int], plan: int, K: int, stream: int = 0) -> None:
+    arr = (ctypes.c_void_p * len(buf_ptrs))(*buf_ptrs)
+    _check(lib.rar_allreduce_chain(arr, plan, K, stream), "rar_allreduce_chain")
+
+
 def rar_autotune(buf_ptrs: Sequence[int], plan: int, stream: int = 0, calls: int = 20) -> float:
     """Returns the winner's mean microseconds per call; the plan keeps the winning B_s, C_s."""
     arr = (ctypes.c_void_p * len(buf_ptrs))(*buf_ptrs)
@@ -213,6 +220,10 @@ def rar_barrier_only(plan: int, stream: int = 0) -> None:
 
 def rar_copy_probe(dst_ptr: int, src_ptr: int, nbytes: int, stream: int = 0) -> None:
     _check(lib.rar_copy_probe(dst_ptr, src_ptr, nbytes, stream), "rar_copy_probe")
+
+
+def rar_read_probe(sink_ptr: int, src_ptr: int, nbytes: int, stream: int = 0) -> None:
+    _check(lib.rar_read_probe(sink_ptr, src_ptr, nbytes, stream), "rar_read_probe")
 
 
 class AllReduce:
@@ -260,6 +271,10 @@ class AllReduce:
     def launch(self, stream=None) -> None:
         """In-place all-reduce of the bound tensors."""
         _check(lib.rar_allreduce(self._bound_ptrs, self.plan, self._stream(stream)), "rar_allreduce")
+
+    def launch_chain(self, K: int, stream=None) -> None:
+        """K in-place all-reduces of the bound tensors, each on the result of the one before, in one launch."""
+        _check(lib.rar_allreduce_chain(self._bound_ptrs, self.plan, K, self._stream(stream)), "rar_allreduce_chain")
 
     def __call__(self, tensors, stream=None) -> None:
         """In-place all-reduce of P tensors of n elements each (one per virtual rank)."""

@@ -132,7 +132,9 @@ struct Shape {
     u64 chunk_stride;        // bytes between S buffers
     u64 flags_offset;
     u64 data_offset;
+    u64 alt_offset;          // second set of S buffers for the odd calls of a chain (0 = none)
     u64 packed_offset;       // data+flag buffers of the packed exchange
+    u64 packed_alt_offset;   // their second set
     u64 packed_stride;
     u64 wait_ticks;          // step-barrier time limit in 100 MHz ticks
     u32 P, G, N, L;
@@ -142,11 +144,13 @@ struct Shape {
     u32 tail;                // elements in the partial last vector (0 = none)
     u32 flag_stride;         // 32-bit words between the flags of consecutive workgroup slots
     u32 B_s;                 // workgroups per rank
-    u32 iters;               // trips per workgroup
+    u32 iters;               // trips per workgroup and call
+    u32 calls;               // all-reduces in this launch (1 unless it is a chain)
 };
 
-__device__ __forceinline__ unsigned char *partial_buf(const Shape &s, u32 level, u32 rank) {
-    return s.scratch + s.data_offset + (static_cast<u64>(level) * s.P + rank) * s.chunk_stride;
+// S_l(rank); set 1 is the second set that the odd calls of a chain use.
+__device__ __forceinline__ unsigned char *partial_buf(const Shape &s, u32 level, u32 rank, u32 set = 0u) {
+    return s.scratch + (set ? s.alt_offset : s.data_offset) + (static_cast<u64>(level) * s.P + rank) * s.chunk_stride;
 }
 
 // Vectors of chunk c that lie inside the message (the last chunks may be short or empty).
@@ -260,8 +264,8 @@ typedef u32 u32x4 __attribute__((ext_vector_type(4)));
 constexpr int kDeviceScope = 16;            // cache-policy bit "sc1"
 constexpr u32 kRawBufferFlags = 0x00020000; // 32-bit raw buffer, no swizzle
 
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t partial_rsrc(const Shape &s, u32 level, u32 rank) {
-    return __builtin_amdgcn_make_buffer_rsrc(partial_buf(s, level, rank), 0, static_cast<u32>(s.chunk_stride),
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t partial_rsrc(const Shape &s, u32 level, u32 rank, u32 set = 0u) {
+    return __builtin_amdgcn_make_buffer_rsrc(partial_buf(s, level, rank, set), 0, static_cast<u32>(s.chunk_stride),
                                              kRawBufferFlags);
 }
 
@@ -317,6 +321,20 @@ __device__ __forceinline__ void publish(u32 *flag, u32 value) {
     __builtin_amdgcn_s_waitcnt(0);  // this wave's write-through stores have completed
     __syncthreads();
     if (threadIdx.x == 0) __hip_atomic_store(flag, value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// A launch in which a wait ran out of time tells the host before it ends: the scratch header
+// (words 2 and 3) holds the device address of a word of pinned host memory (0 = none) that the
+// host reads, without any synchronisation, before it enqueues the plan's next launch.  (Word 0 of
+// the header is the status word that makes all other waits on the device give up quickly.)
+__device__ __forceinline__ void tell_host(const Shape &s, bool gave_up) {
+    if (gave_up) {
+        const u32 *header = reinterpret_cast<const u32 *>(s.scratch);
+        const u64 lo = __hip_atomic_load(header + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const u64 hi = __hip_atomic_load(header + 3, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        u32 *host_word = reinterpret_cast<u32 *>(lo | (hi << 32));
+        if (host_word) __hip_atomic_store(host_word, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
 }
 
 // Thread 0 polls; the wait is bounded by wall-clock time and by the shared status word, so
@@ -385,8 +403,22 @@ __device__ __forceinline__ void locate(const Shape &s, u32 block, u32 &r_n, u32 
 // reuse of places); FULL = true the launch whose slices are all whole slices inside the message
 // (the host checks it: no ragged chunk, no tail, no trip past the chunk).  Each measured 1-5 %
 // faster than the run-time branches.
-template <int DT, int GT, int U, bool DATA, bool FOLD, bool ONE, bool FULL>
+//
+// CHAIN = true runs s.calls all-reduces one after the other, each on the result of the one
+// before (Section 4.2.1 and 4.2.3: a rank goes on to its next call without waiting for the
+// others to finish this one).  A workgroup's slices are the same in every call, and chunk c of
+// the G buffers of a node is read (reduce-scatter) and written (all-gather) by rank (r_n, c)
+// alone, so what a workgroup reads in call k+1 is what the same threads wrote in call k: no
+// barrier between calls.  The trips of all calls form one sequence T = 0, 1, ..: the flag
+// tickets just keep counting, and an exchange buffer is written again only two trips (or two
+// calls) later, in the other of two places: the odd calls use the second set of buffers if the
+// plan has one, else trip T uses place T mod 2 of the workgroup's two places in the first set
+// (the host narrows B_s so that they fit).  By then the reader of the old contents is done:
+// the writer has since waited, at the same step of the trip in between, for a flag that this
+// reader raises only after the trip in which it read.
+template <int DT, int GT, int U, bool DATA, bool FOLD, bool ONE, bool FULL, bool CHAIN>
 __global__ __launch_bounds__(kThreads) void fused_kernel(RankPtrs bufs, Shape s) {
+    static_assert(!(CHAIN && ONE), "a chain makes several trips");
     u32 r_n, c, w;
     locate(s, blockIdx.x, r_n, c, w);
     const u32 G = GT ? GT : s.G;
@@ -404,21 +436,28 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(RankPtrs bufs, Shape s)
     const bool idle = sits_out(r_n, fold), takes_in = folds_in(r_n, fold);
 
     const u32 trips = ONE ? 1u : s.iters;
-    for (u32 it = 0; it < trips; ++it) {
+    const u32 calls = CHAIN ? s.calls : 1u;
+    const bool two_sets = CHAIN && s.alt_offset != 0;
+    u32 T = 0u;  // trips made so far, over all calls of the launch
+    for (u32 k = 0; k < calls; ++k) {
+    for (u32 it = 0; it < trips; ++it, ++T) {
         const u32 slice = w + it * s.B_s;
         const u64 first = static_cast<u64>(slice) * (kThreads * U);
         const u32 v0 = static_cast<u32>(first) + threadIdx.x;  // first < 2^31 by construction
         const bool whole = FULL || first + kThreads * U <= whole_vecs;
         const u32 valid = FULL ? s.chunk_vecs : (first < valid_vecs ? valid_vecs : 0u);  // slices past the chunk do nothing
-        const u32 ticket = base + it + 1u;
+        const u32 ticket = base + T + 1u;
         // Where the slice lives in a partial buffer.  With one or two trips every slice has its
         // own place.  With three or more, a workgroup alternates between two places of its own
         // (2*B_s*C_s bytes per buffer, which is less than a chunk then): a place is rewritten
         // two trips later, and by then its reader is done with it, because this workgroup has
         // since waited for that reader's next trip at the same step, which the reader starts
         // only after finishing the trip in which it read the place.  The smaller footprint keeps
-        // the exchange inside the memory-side cache however long the message is.
-        const u32 s0 = !ONE && s.iters >= 3u ? (w * 2u + (it & 1u)) * (kThreads * U) + threadIdx.x : v0;
+        // the exchange inside the memory-side cache however long the message is.  A chain does
+        // the same across its calls (see above).
+        const u32 ring = (w * 2u + (T & 1u)) * (kThreads * U) + threadIdx.x;
+        const u32 s0 = CHAIN ? (two_sets ? v0 : ring) : (!ONE && s.iters >= 3u ? ring : v0);
+        const u32 set = two_sets ? (k & 1u) : 0u;
 
         uint4 part[U];
         if (DATA) reduce_scatter_slice<DT, GT, U>(bufs, s, r_n, c, v0, valid, whole, part);
@@ -427,36 +466,38 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(RankPtrs bufs, Shape s)
                 wait_for(s, flag_ptr(s, 0, p - G, w), ticket, gave_up);
                 if (DATA) {
                     uint4 got[U];
-                    load_slice_coherent<U>(partial_rsrc(s, 0, p - G), s0, v0, valid, whole, got);
+                    load_slice_coherent<U>(partial_rsrc(s, 0, p - G, set), s0, v0, valid, whole, got);
 #pragma unroll
                     for (int u = 0; u < U; ++u) part[u] = combine<DT>(got[u], part[u]);
                 }
             }
-            if (DATA) store_slice_coherent<U>(partial_rsrc(s, 0, p), s0, v0, valid, whole, part);
+            if (DATA) store_slice_coherent<U>(partial_rsrc(s, 0, p, set), s0, v0, valid, whole, part);
             publish(flag_ptr(s, 0, p, w), ticket);
         }
         if (idle) {  // no steps: the odd partner's S_L is the result
             wait_for(s, flag_ptr(s, s.L, p + G, w), ticket, gave_up);
-            if (DATA) load_slice_coherent<U>(partial_rsrc(s, s.L, p + G), s0, v0, valid, whole, part);
+            if (DATA) load_slice_coherent<U>(partial_rsrc(s, s.L, p + G, set), s0, v0, valid, whole, part);
         } else {
             for (u32 l = 0; l < s.L; ++l) {
                 const u32 peer = peer_node(r_n, l, fold) * G + c;
                 wait_for(s, flag_ptr(s, l, peer, w), ticket, gave_up);
                 if (DATA) {
                     uint4 got[U];
-                    load_slice_coherent<U>(partial_rsrc(s, l, peer), s0, v0, valid, whole, got);
+                    load_slice_coherent<U>(partial_rsrc(s, l, peer, set), s0, v0, valid, whole, got);
 #pragma unroll
                     for (int u = 0; u < U; ++u) part[u] = combine<DT>(got[u], part[u]);
                 }
                 // the last step's result is exchanged only if a partner that sat out needs it
                 if (l + 1 < s.L || takes_in) {
-                    if (DATA) store_slice_coherent<U>(partial_rsrc(s, l + 1, p), s0, v0, valid, whole, part);
+                    if (DATA) store_slice_coherent<U>(partial_rsrc(s, l + 1, p, set), s0, v0, valid, whole, part);
                     publish(flag_ptr(s, l + 1, p, w), ticket);
                 }
             }
         }
         if (DATA) all_gather_slice<DT, GT, U>(bufs, s, r_n, c, v0, valid, whole, part);
     }
+    }
+    tell_host(s, gave_up);
 }
 
 // ---- the fused schedule with data+flag words (Section 4.2.2, the low-latency payload) -------
@@ -478,8 +519,8 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(RankPtrs bufs, Shape s)
 // the kernel ends, and a captured graph can replay the call.  Buffers start zero-filled; zero
 // is never used as a number.
 
-__device__ __forceinline__ u64 *packed_buf(const Shape &s, u32 level, u32 rank) {
-    return reinterpret_cast<u64 *>(s.scratch + s.packed_offset +
+__device__ __forceinline__ u64 *packed_buf(const Shape &s, u32 level, u32 rank, u32 set = 0u) {
+    return reinterpret_cast<u64 *>(s.scratch + (set ? s.packed_alt_offset : s.packed_offset) +
                                    (static_cast<u64>(level) * s.P + rank) * s.packed_stride);
 }
 
@@ -536,8 +577,16 @@ __device__ __forceinline__ void load_slice_packed(const Shape &s, const u64 *buf
     }
 }
 
-template <int DT, int GT, int U, bool FOLD, bool ONE, bool FULL>
+// CHAIN = true: s.calls all-reduces in one launch, as in fused_kernel.  The even calls use the
+// first set of data+flag buffers and the odd calls the second, each set with its own sequence
+// numbers (a set advances by one per call that uses it, on every rank alike).  A word is
+// overwritten two calls later; the thread that read its old contents is done by then, because the
+// writing thread has meanwhile, in the call in between, consumed a word that this reader
+// wrote after it was done reading (the exchange pairs thread t of one rank with thread t of the
+// other, in both directions).
+template <int DT, int GT, int U, bool FOLD, bool ONE, bool FULL, bool CHAIN>
 __global__ __launch_bounds__(kThreads) void fused_packed_kernel(RankPtrs bufs, Shape s) {
+    static_assert(!(CHAIN && ONE), "a chain makes several trips");
     u32 r_n, c, w;
     locate(s, blockIdx.x, r_n, c, w);
     const u32 G = GT ? GT : s.G;
@@ -552,6 +601,9 @@ __global__ __launch_bounds__(kThreads) void fused_packed_kernel(RankPtrs bufs, S
     const bool idle = sits_out(r_n, fold), takes_in = folds_in(r_n, fold);
 
     const u32 trips = ONE ? 1u : s.iters;
+    const u32 calls = CHAIN ? s.calls : 1u;
+    for (u32 k = 0; k < calls; ++k) {
+    const u32 set = CHAIN ? (k & 1u) : 0u;
     for (u32 it = 0; it < trips; ++it) {
         const u32 slice = w + it * s.B_s;
         const u64 first = static_cast<u64>(slice) * (kThreads * U);
@@ -562,7 +614,7 @@ __global__ __launch_bounds__(kThreads) void fused_packed_kernel(RankPtrs bufs, S
         // thread without a word in this slice neither writes nor waits)
         u32 seq = 0u;
         if (s.L && (whole || v0 < valid)) {
-            const u64 *own = packed_buf(s, 0, p) + static_cast<u64>(slice) * (kThreads * U * 4) + threadIdx.x;
+            const u64 *own = packed_buf(s, 0, p, set) + static_cast<u64>(slice) * (kThreads * U * 4) + threadIdx.x;
             seq = static_cast<u32>(__hip_atomic_load(own, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >> 32);
         }
         seq += 1u;
@@ -573,27 +625,29 @@ __global__ __launch_bounds__(kThreads) void fused_packed_kernel(RankPtrs bufs, S
         if (valid != 0u && s.L) {  // uniform over the workgroup; a slice past the chunk exchanges nothing
             if (takes_in) {  // the even partner's reduce-scatter result joins before the steps
                 uint4 got[U];
-                load_slice_packed<U>(s, packed_buf(s, 0, p - G), slice, v0, valid, whole, seq, gave_up, got);
+                load_slice_packed<U>(s, packed_buf(s, 0, p - G, set), slice, v0, valid, whole, seq, gave_up, got);
 #pragma unroll
                 for (int u = 0; u < U; ++u) part[u] = combine<DT>(got[u], part[u]);
             }
-            store_slice_packed<U>(packed_buf(s, 0, p), slice, v0, valid, whole, seq, part);
+            store_slice_packed<U>(packed_buf(s, 0, p, set), slice, v0, valid, whole, seq, part);
             if (idle) {  // no steps: the odd partner's last partial is the result
-                load_slice_packed<U>(s, packed_buf(s, s.L, p + G), slice, v0, valid, whole, seq, gave_up, part);
+                load_slice_packed<U>(s, packed_buf(s, s.L, p + G, set), slice, v0, valid, whole, seq, gave_up, part);
             } else {
                 for (u32 l = 0; l < s.L; ++l) {
                     const u32 peer = peer_node(r_n, l, fold) * G + c;
                     uint4 got[U];
-                    load_slice_packed<U>(s, packed_buf(s, l, peer), slice, v0, valid, whole, seq, gave_up, got);
+                    load_slice_packed<U>(s, packed_buf(s, l, peer, set), slice, v0, valid, whole, seq, gave_up, got);
 #pragma unroll
                     for (int u = 0; u < U; ++u) part[u] = combine<DT>(got[u], part[u]);
                     if (l + 1 < s.L || takes_in)
-                        store_slice_packed<U>(packed_buf(s, l + 1, p), slice, v0, valid, whole, seq, part);
+                        store_slice_packed<U>(packed_buf(s, l + 1, p, set), slice, v0, valid, whole, seq, part);
                 }
             }
         }
         all_gather_slice<DT, GT, U>(bufs, s, r_n, c, v0, valid, whole, part);
     }
+    }
+    tell_host(s, gave_up);
 }
 
 // ---- stepwise kernels: one launch per phase, one slice per workgroup -------------------------
@@ -691,9 +745,12 @@ __global__ __launch_bounds__(kThreads) void combine_kernel(unsigned char *dst, c
 
 // ---- small utilities ---------------------------------------------------------------------------
 
-__global__ __launch_bounds__(kThreads) void fill_zero_kernel(u32 *words, u64 count) {
+// Zero `count` words; words 2 and 3 receive `at_word_2` instead (the scratch header keeps the
+// device address of the host's time-out word there; 0 when a plain zero fill is wanted).
+__global__ __launch_bounds__(kThreads) void fill_zero_kernel(u32 *words, u64 count, u64 at_word_2) {
     const u64 stride = static_cast<u64>(gridDim.x) * kThreads;
-    for (u64 i = static_cast<u64>(blockIdx.x) * kThreads + threadIdx.x; i < count; i += stride) words[i] = 0u;
+    for (u64 i = static_cast<u64>(blockIdx.x) * kThreads + threadIdx.x; i < count; i += stride)
+        words[i] = i == 2 ? static_cast<u32>(at_word_2) : i == 3 ? static_cast<u32>(at_word_2 >> 32) : 0u;
 }
 
 __global__ __launch_bounds__(kThreads) void empty_kernel() {}
@@ -701,6 +758,19 @@ __global__ __launch_bounds__(kThreads) void empty_kernel() {}
 __global__ __launch_bounds__(kThreads) void copy_kernel(uint4 *dst, const uint4 *src, u64 vecs) {
     const u64 stride = static_cast<u64>(gridDim.x) * kThreads;
     for (u64 v = static_cast<u64>(blockIdx.x) * kThreads + threadIdx.x; v < vecs; v += stride) dst[v] = src[v];
+}
+
+// Reads only: every thread folds the vectors it loads into one value, and one thread per
+// workgroup whose value happens to be all ones stores it (so the loads cannot be dropped, and in
+// practice nothing is written).
+__global__ __launch_bounds__(kThreads) void read_kernel(uint4 *sink, const uint4 *src, u64 vecs) {
+    const u64 stride = static_cast<u64>(gridDim.x) * kThreads;
+    uint4 acc = make_uint4(0u, 0u, 0u, 0u);
+    for (u64 v = static_cast<u64>(blockIdx.x) * kThreads + threadIdx.x; v < vecs; v += stride) {
+        const uint4 t = src[v];
+        acc.x ^= t.x; acc.y ^= t.y; acc.z ^= t.z; acc.w ^= t.w;
+    }
+    if ((acc.x & acc.y & acc.z & acc.w) == 0xffffffffu) *sink = acc;
 }
 
 // ---- launchers ---------------------------------------------------------------------------------
@@ -712,7 +782,9 @@ static Shape make_shape(const rar_plan_t &plan, const Tuning &t) {
     s.chunk_stride = g.chunk_stride;
     s.flags_offset = g.flags_offset;
     s.data_offset = g.data_offset;
+    s.alt_offset = g.alt_offset;
     s.packed_offset = g.packed_offset;
+    s.packed_alt_offset = g.packed_alt_offset;
     s.packed_stride = g.packed_stride;
     s.wait_ticks = plan.wait_limit_us * 100ull;  // the wall clock counts at 100 MHz
     s.P = g.P; s.G = g.G; s.N = g.N; s.L = g.L;
@@ -722,6 +794,7 @@ static Shape make_shape(const rar_plan_t &plan, const Tuning &t) {
     s.tail = static_cast<u32>(g.n % g.per_vec);
     s.B_s = t.B_s;
     s.iters = t.iters;
+    s.calls = 1;
     // One flag per 64 bytes where the words allow it (measured: barrier time -15..25 %, whole call
     // -1..3 % from 256 workgroups up; small grids are better off with 32 bytes).
     const u32 widest = static_cast<u32>(g.P) * t.B_s >= 256u ? 16u : 8u;
@@ -741,67 +814,78 @@ struct Variant {
     bool fold;   // N is not a power of two
     bool one;    // every workgroup makes a single trip
     bool full;   // every slice of the launch is a whole slice inside the message
+    bool chain;  // several all-reduces in one launch
 };
 
-template <int DT, int GT, bool DATA, bool FOLD, bool ONE, bool FULL>
+template <int DT, int GT, bool DATA, bool FOLD, bool ONE, bool FULL, bool CHAIN>
 static FusedFn pick_unroll(int unroll) {
     switch (unroll) {
-        case 1: return fused_kernel<DT, GT, 1, DATA, FOLD, ONE, FULL>;
-        case 2: return fused_kernel<DT, GT, 2, DATA, FOLD, ONE, FULL>;
-        case 4: return fused_kernel<DT, GT, 4, DATA, FOLD, ONE, FULL>;
-        default: return fused_kernel<DT, GT, 8, DATA, FOLD, ONE, FULL>;
+        case 1: return fused_kernel<DT, GT, 1, DATA, FOLD, ONE, FULL, CHAIN>;
+        case 2: return fused_kernel<DT, GT, 2, DATA, FOLD, ONE, FULL, CHAIN>;
+        case 4: return fused_kernel<DT, GT, 4, DATA, FOLD, ONE, FULL, CHAIN>;
+        default: return fused_kernel<DT, GT, 8, DATA, FOLD, ONE, FULL, CHAIN>;
     }
 }
-template <int DT, bool DATA, bool ONE, bool FULL>
+template <int DT, bool DATA, bool ONE, bool FULL, bool CHAIN>
 static FusedFn pick_group(int G, int unroll) {
     switch (G) {
-        case 1: return pick_unroll<DT, 1, DATA, false, ONE, FULL>(unroll);
-        case 2: return pick_unroll<DT, 2, DATA, false, ONE, FULL>(unroll);
-        case 4: return pick_unroll<DT, 4, DATA, false, ONE, FULL>(unroll);
-        case 8: return pick_unroll<DT, 8, DATA, false, ONE, FULL>(unroll);
-        default: return pick_unroll<DT, 0, DATA, false, false, false>(unroll);
+        case 1: return pick_unroll<DT, 1, DATA, false, ONE, FULL, CHAIN>(unroll);
+        case 2: return pick_unroll<DT, 2, DATA, false, ONE, FULL, CHAIN>(unroll);
+        case 4: return pick_unroll<DT, 4, DATA, false, ONE, FULL, CHAIN>(unroll);
+        case 8: return pick_unroll<DT, 8, DATA, false, ONE, FULL, CHAIN>(unroll);
+        default: return pick_unroll<DT, 0, DATA, false, false, false, CHAIN>(unroll);
     }
 }
 template <int DT>
 static FusedFn pick_special(const Variant &v) {
-    if (v.fold) return pick_unroll<DT, 0, true, true, false, false>(v.unroll);
-    if (v.one) return v.full ? pick_group<DT, true, true, true>(v.G, v.unroll) : pick_group<DT, true, true, false>(v.G, v.unroll);
-    return v.full ? pick_group<DT, true, false, true>(v.G, v.unroll) : pick_group<DT, true, false, false>(v.G, v.unroll);
+    if (v.chain) {
+        if (v.fold) return pick_unroll<DT, 0, true, true, false, false, true>(v.unroll);
+        return v.full ? pick_group<DT, true, false, true, true>(v.G, v.unroll) : pick_group<DT, true, false, false, true>(v.G, v.unroll);
+    }
+    if (v.fold) return pick_unroll<DT, 0, true, true, false, false, false>(v.unroll);
+    if (v.one)
+        return v.full ? pick_group<DT, true, true, true, false>(v.G, v.unroll) : pick_group<DT, true, true, false, false>(v.G, v.unroll);
+    return v.full ? pick_group<DT, true, false, true, false>(v.G, v.unroll) : pick_group<DT, true, false, false, false>(v.G, v.unroll);
 }
 template <int DT>
 static FusedFn pick_barrier_only(const Variant &v) {  // a measurement aid: the generic instances are enough
-    if (v.fold) return pick_unroll<DT, 0, false, true, false, false>(v.unroll);
-    return pick_group<DT, false, false, false>(v.G, v.unroll);
+    if (v.fold) return pick_unroll<DT, 0, false, true, false, false, false>(v.unroll);
+    return pick_group<DT, false, false, false, false>(v.G, v.unroll);
 }
 static FusedFn pick_fused(const Variant &v) {
     if (v.dtype == RAR_BF16) return v.data ? pick_special<RAR_BF16>(v) : pick_barrier_only<RAR_BF16>(v);
     return v.data ? pick_special<RAR_F32>(v) : pick_barrier_only<RAR_F32>(v);
 }
 
-template <int DT, int GT, bool FOLD, bool ONE, bool FULL>
+template <int DT, int GT, bool FOLD, bool ONE, bool FULL, bool CHAIN>
 static FusedFn pick_packed_unroll(int unroll) {
     switch (unroll) {
-        case 1: return fused_packed_kernel<DT, GT, 1, FOLD, ONE, FULL>;
-        case 2: return fused_packed_kernel<DT, GT, 2, FOLD, ONE, FULL>;
-        case 4: return fused_packed_kernel<DT, GT, 4, FOLD, ONE, FULL>;
-        default: return fused_packed_kernel<DT, GT, 8, FOLD, ONE, FULL>;
+        case 1: return fused_packed_kernel<DT, GT, 1, FOLD, ONE, FULL, CHAIN>;
+        case 2: return fused_packed_kernel<DT, GT, 2, FOLD, ONE, FULL, CHAIN>;
+        case 4: return fused_packed_kernel<DT, GT, 4, FOLD, ONE, FULL, CHAIN>;
+        default: return fused_packed_kernel<DT, GT, 8, FOLD, ONE, FULL, CHAIN>;
     }
 }
-template <int DT, bool ONE, bool FULL>
+template <int DT, bool ONE, bool FULL, bool CHAIN>
 static FusedFn pick_packed_group(int G, int unroll) {
     switch (G) {
-        case 1: return pick_packed_unroll<DT, 1, false, ONE, FULL>(unroll);
-        case 2: return pick_packed_unroll<DT, 2, false, ONE, FULL>(unroll);
-        case 4: return pick_packed_unroll<DT, 4, false, ONE, FULL>(unroll);
-        case 8: return pick_packed_unroll<DT, 8, false, ONE, FULL>(unroll);
-        default: return pick_packed_unroll<DT, 0, false, false, false>(unroll);
+        case 1: return pick_packed_unroll<DT, 1, false, ONE, FULL, CHAIN>(unroll);
+        case 2: return pick_packed_unroll<DT, 2, false, ONE, FULL, CHAIN>(unroll);
+        case 4: return pick_packed_unroll<DT, 4, false, ONE, FULL, CHAIN>(unroll);
+        case 8: return pick_packed_unroll<DT, 8, false, ONE, FULL, CHAIN>(unroll);
+        default: return pick_packed_unroll<DT, 0, false, false, false, CHAIN>(unroll);
     }
 }
 template <int DT>
 static FusedFn pick_packed_special(const Variant &v) {
-    if (v.fold) return pick_packed_unroll<DT, 0, true, false, false>(v.unroll);
-    if (v.one) return v.full ? pick_packed_group<DT, true, true>(v.G, v.unroll) : pick_packed_group<DT, true, false>(v.G, v.unroll);
-    return v.full ? pick_packed_group<DT, false, true>(v.G, v.unroll) : pick_packed_group<DT, false, false>(v.G, v.unroll);
+    if (v.chain) {
+        if (v.fold) return pick_packed_unroll<DT, 0, true, false, false, true>(v.unroll);
+        return v.full ? pick_packed_group<DT, false, true, true>(v.G, v.unroll) : pick_packed_group<DT, false, false, true>(v.G, v.unroll);
+    }
+    if (v.fold) return pick_packed_unroll<DT, 0, true, false, false, false>(v.unroll);
+    if (v.one)
+        return v.full ? pick_packed_group<DT, true, true, false>(v.G, v.unroll) : pick_packed_group<DT, true, false, false>(v.G, v.unroll);
+    return v.full ? pick_packed_group<DT, false, true, false>(v.G, v.unroll) : pick_packed_group<DT, false, false, false>(v.G, v.unroll);
 }
 static FusedFn pick_packed(const Variant &v) {
     return v.dtype == RAR_BF16 ? pick_packed_special<RAR_BF16>(v) : pick_packed_special<RAR_F32>(v);
@@ -834,7 +918,7 @@ int device_info(DeviceInfo *out) {
     return RAR_OK;
 }
 
-int fused_max_resident(int dtype, int G, int unroll, bool packed, bool fold, long *out) {
+int fused_max_resident(int dtype, int G, int unroll, bool packed, bool fold, bool chain, long *out) {
     DeviceInfo info;
     int rc = device_info(&info);
     if (rc != RAR_OK) return rc;
@@ -842,14 +926,21 @@ int fused_max_resident(int dtype, int G, int unroll, bool packed, bool fold, lon
     // a launch will make
     int fewest = 0;
     for (int k = 0; k < 4; ++k) {
-        const Variant v{dtype, G, unroll, true, fold, (k & 1) != 0, (k & 2) != 0};
+        const bool one = (k & 1) != 0;
+        if (chain && one) continue;
+        const Variant v{dtype, G, unroll, true, fold, one, (k & 2) != 0, chain};
         FusedFn fn = packed ? pick_packed(v) : pick_fused(v);
         int per_cu = 0;
         if (note_hip(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(fn), kThreads, 0)) !=
                 hipSuccess || per_cu < 1)
             return RAR_ERR_HIP;
-        if (k == 0 || per_cu < fewest) fewest = per_cu;
+        if (fewest == 0 || per_cu < fewest) fewest = per_cu;
     }
+    // The query is arithmetic on the kernel's register counts.  Where vector registers set the
+    // figure it is exact; a figure of 7 or 8 per compute unit can be set by scalar registers or
+    // wave slots, of which the hardware may keep some for itself, so such a figure is taken one
+    // lower.  (The planner never goes beyond kMaxWorkgroupsPerCU anyway.)
+    if (fewest >= 7) fewest -= 1;
     *out = static_cast<long>(fewest) * info.compute_units;
     return RAR_OK;
 }
@@ -859,13 +950,14 @@ int fused_max_resident(int dtype, int G, int unroll, bool packed, bool fold, lon
 static void begin_launch() { (void)hipGetLastError(); }
 static int check_launch() { return note_hip(hipGetLastError()) == hipSuccess ? RAR_OK : RAR_ERR_HIP; }
 
-int launch_fill_zero(void *words, size_t bytes, hipStream_t stream) {
+int launch_fill_zero(void *words, size_t bytes, const void *at_word_2, hipStream_t stream) {
     begin_launch();
     const u64 count = bytes / 4;
     u64 blocks = (count + kThreads - 1) / kThreads;
     if (blocks > 1024) blocks = 1024;
     if (blocks == 0) return RAR_OK;
-    fill_zero_kernel<<<dim3(static_cast<u32>(blocks)), dim3(kThreads), 0, stream>>>(static_cast<u32 *>(words), count);
+    fill_zero_kernel<<<dim3(static_cast<u32>(blocks)), dim3(kThreads), 0, stream>>>(static_cast<u32 *>(words), count,
+                                                                                     reinterpret_cast<u64>(at_word_2));
     return check_launch();
 }
 
@@ -877,22 +969,30 @@ static bool all_slices_whole(const Geometry &g, const Tuning &t) {
            static_cast<size_t>(t.B_s) * t.iters * slice == g.chunk_vecs;
 }
 
-int launch_fused(const rar_plan_t &plan, const RankPtrs &bufs, const Tuning &t, bool data, hipStream_t stream) {
+// `scratch` is the memory the launch works on: the plan's own, or the library's static array.
+// calls = 0: one all-reduce (the plain instances); calls >= 1: a chain of that many.
+int launch_fused(const rar_plan_t &plan, void *scratch, const RankPtrs &bufs, const Tuning &t, bool data, int calls,
+                 hipStream_t stream) {
     begin_launch();
     const Geometry &g = plan.geo;
-    const Shape s = make_shape(plan, t);
+    Shape s = make_shape(plan, t);
+    s.scratch = static_cast<unsigned char *>(scratch);
+    const bool chain = calls > 0;
+    if (chain) s.calls = static_cast<u32>(calls);
     const u32 grid = static_cast<u32>(g.P) * t.B_s;
-    FusedFn fn = pick_fused(Variant{g.dtype, g.G, t.unroll, data, g.fold != 0, t.iters == 1, all_slices_whole(g, t)});
+    FusedFn fn = pick_fused(Variant{g.dtype, g.G, t.unroll, data, g.fold != 0, !chain && t.iters == 1, all_slices_whole(g, t), chain});
     fn<<<dim3(grid), dim3(kThreads), 0, stream>>>(bufs, s);
     return check_launch();
 }
 
-int launch_fused_packed(const rar_plan_t &plan, const RankPtrs &bufs, const Tuning &t, hipStream_t stream) {
+int launch_fused_packed(const rar_plan_t &plan, const RankPtrs &bufs, const Tuning &t, int calls, hipStream_t stream) {
     begin_launch();
     const Geometry &g = plan.geo;
-    const Shape s = make_shape(plan, t);
+    Shape s = make_shape(plan, t);
+    const bool chain = calls > 0;
+    if (chain) s.calls = static_cast<u32>(calls);
     const u32 grid = static_cast<u32>(g.P) * t.B_s;
-    FusedFn fn = pick_packed(Variant{g.dtype, g.G, t.unroll, true, g.fold != 0, t.iters == 1, all_slices_whole(g, t)});
+    FusedFn fn = pick_packed(Variant{g.dtype, g.G, t.unroll, true, g.fold != 0, !chain && t.iters == 1, all_slices_whole(g, t), chain});
     fn<<<dim3(grid), dim3(kThreads), 0, stream>>>(bufs, s);
     return check_launch();
 }
@@ -946,6 +1046,16 @@ int launch_combine(void *dst, const void *src, size_t full_vecs, unsigned tail, 
     else
         combine_kernel<RAR_F32><<<grid, block, 0, stream>>>(static_cast<unsigned char *>(dst),
                                                             static_cast<const unsigned char *>(src), full_vecs, tail);
+    return check_launch();
+}
+
+int launch_read(void *sink, const void *src, size_t vecs, hipStream_t stream) {
+    begin_launch();
+    u64 blocks = (vecs + kThreads - 1) / kThreads;
+    if (blocks == 0) return RAR_OK;
+    if (blocks > 16384) blocks = 16384;
+    read_kernel<<<dim3(static_cast<u32>(blocks)), dim3(kThreads), 0, stream>>>(static_cast<uint4 *>(sink),
+                                                                               static_cast<const uint4 *>(src), vecs);
     return check_launch();
 }
 

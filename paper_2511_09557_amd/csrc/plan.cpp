@@ -38,7 +38,8 @@ int make_geometry(int P, int G, size_t n, int dtype, Geometry *geo) {
     // power of two (it carries the result back to the nodes that sat out).
     g.flags_bytes = round_up(static_cast<size_t>(L + 1) * P * kMaxWorkgroupsPerRank * 4, kAlign);
     g.data_offset = g.flags_offset + g.flags_bytes;
-    g.scratch_bytes = g.data_offset + static_cast<size_t>(L + 1) * P * g.chunk_stride;
+    g.fused_bytes = g.data_offset + static_cast<size_t>(L + 1) * P * g.chunk_stride;
+    g.scratch_bytes = g.fused_bytes;
     // Data+flag buffers for the packed exchange: one per (step l < L, rank), twice a chunk; one
     // more per rank if N is not a power of two (the last partial goes back to a node that sat out).
     if (L > 0 && g.chunk_vecs * 16 <= kPackedMaxChunkBytes) {
@@ -48,6 +49,12 @@ int make_geometry(int P, int G, size_t n, int dtype, Geometry *geo) {
         // slice is strided by thread, so a ragged last slice still spans its full extent
         g.packed_stride = round_up(g.chunk_vecs, static_cast<size_t>(kThreads) * 8) * 32;
         g.scratch_bytes = g.packed_offset + static_cast<size_t>(g.packed_levels) * P * g.packed_stride;
+        // Chained calls (rar_allreduce_chain) reuse an exchange buffer two calls later: a second
+        // set of both kinds of buffers for the odd calls.  Only for these short chunks; longer
+        // ones alternate between two places inside the first set instead.
+        g.alt_offset = g.scratch_bytes;
+        g.packed_alt_offset = g.alt_offset + static_cast<size_t>(L + 1) * P * g.chunk_stride;
+        g.scratch_bytes = g.packed_alt_offset + static_cast<size_t>(g.packed_levels) * P * g.packed_stride;
     }
     *geo = g;
     return RAR_OK;
@@ -55,13 +62,16 @@ int make_geometry(int P, int G, size_t n, int dtype, Geometry *geo) {
 
 Tuning resolve_tuning(const rar_plan_t &plan, const long *max_resident) {
     const Geometry &g = plan.geo;
+    const long units = plan.compute_units > 0 ? plan.compute_units : 256;
     auto cap_for = [&](int unroll_index) {
         long cap = kMaxWorkgroupsPerRank;
-        if (max_resident && max_resident[unroll_index] > 0) {
-            long fit = max_resident[unroll_index] / plan.concurrency / g.P;
-            if (fit < 1) fit = 1;
-            if (fit < cap) cap = fit;
-        }
+        // never wider than kMaxWorkgroupsPerCU per compute unit, nor than what the device holds at once
+        long whole = kMaxWorkgroupsPerCU * units;
+        if (max_resident && max_resident[unroll_index] > 0 && max_resident[unroll_index] < whole)
+            whole = max_resident[unroll_index];
+        long fit = whole / plan.concurrency / g.P;
+        if (fit < 1) fit = 1;
+        if (fit < cap) cap = fit;
         return cap;
     };
     const size_t V = g.chunk_vecs;
@@ -78,7 +88,7 @@ Tuning resolve_tuning(const rar_plan_t &plan, const long *max_resident) {
     // workgroups per compute unit (32 KiB trips when a rank reads at most two buffers per
     // element, so that a thread still has 16 loads in flight; half the workgroups when it
     // reads eight or more).
-    const long target = 4L * (plan.compute_units > 0 ? plan.compute_units : 256) / plan.concurrency;
+    const long target = 4L * units / plan.concurrency;
     const long small_target = g.L >= 4 ? target / 2 : target;
     long grid_cap = kMaxWorkgroupsPerRank;  // workgroups per rank beyond which the built-in choice does not go
     Tuning t{};
@@ -117,13 +127,28 @@ Tuning resolve_tuning(const rar_plan_t &plan, const long *max_resident) {
     return t;
 }
 
+Tuning resolve_chain_tuning(const rar_plan_t &plan, const long *max_resident) {
+    Tuning t = resolve_tuning(plan, max_resident);
+    const Geometry &g = plan.geo;
+    if (g.L == 0 || g.alt_offset != 0) return t;  // nothing is exchanged, or the odd calls have their own buffers
+    // Two places per workgroup inside one partial buffer: 2 * B_s slices must fit in a chunk.
+    const size_t slice = static_cast<size_t>(kThreads) * t.unroll;
+    const size_t all = (g.chunk_vecs + slice - 1) / slice;
+    size_t fit = g.chunk_stride / 16 / slice / 2;
+    if (fit < 1) fit = 1;  // cannot happen: a plan without a second set has chunks of more than 256 KiB
+    if (static_cast<size_t>(t.B_s) > fit) t.B_s = static_cast<int>(fit);
+    t.iters = static_cast<int>((all + t.B_s - 1) / t.B_s);
+    if (t.iters < 1) t.iters = 1;
+    return t;
+}
+
 }  // namespace rar
 
 using rar::Geometry;
 
 extern "C" {
 
-int rar_version(void) { return 100; }
+int rar_version(void) { return 200; }
 
 const char *rar_strerror(int status) {
     switch (status) {
@@ -137,6 +162,7 @@ const char *rar_strerror(int status) {
         case RAR_ERR_HIP: return "HIP call failed";
         case RAR_ERR_TIMEOUT: return "step barrier wait timed out";
         case RAR_ERR_TUNING: return "unsupported B_s / C_s";
+        case RAR_ERR_CAPTURE: return "first call of a plan (or first after a time-out) made during stream capture";
         default: return "unknown status";
     }
 }
@@ -155,6 +181,7 @@ int rar_plan(int P, int G, size_t n, int dtype, rar_plan_t **out) {
 }
 
 int rar_plan_free(rar_plan_t *plan) {
+    if (plan && plan->host_status && plan->release_host_status) plan->release_host_status(plan->host_status);
     delete plan;
     return RAR_OK;
 }

@@ -12,6 +12,14 @@ namespace rar {
 
 constexpr int kThreads = 256;           // threads per workgroup of every kernel
 constexpr int kMaxWorkgroupsPerRank = 256;
+// No fused launch is wider than this many workgroups per compute unit, whatever the occupancy
+// query says.  The step barriers spin, so the whole grid has to be resident at once, and the
+// query's figure is arithmetic on register counts with no margin: launches sized exactly to it
+// (7 per compute unit, a figure set by scalar registers) once ended in step-barrier time-outs on
+// one machine.  Four per compute unit is also where the measured optimum lies: more workgroups
+// only add step barriers.
+constexpr int kMaxWorkgroupsPerCU = 4;
+constexpr int kMaxChainCalls = 1 << 16; // calls in one rar_allreduce_chain launch
 constexpr size_t kHeaderBytes = 256;    // scratch header: status word at offset 0
 constexpr size_t kAlign = 256;
 // The fused data+flag exchange doubles the exchanged bytes, so it is offered for small messages
@@ -36,6 +44,12 @@ struct Geometry {
     size_t packed_offset = 0;  // byte offset of the data+flag buffers (0 = the plan has none)
     size_t packed_stride = 0;  // bytes of one data+flag buffer: 2 * chunk bytes, rounded
     int packed_levels = 0;     // data+flag buffers per rank: L, or L + 1 if N is not a power of two
+    // A second set of exchange buffers, used by the odd calls of a chained launch (0 = none: the
+    // plan's chunks are too long for it, and a chain then alternates between two places inside
+    // the first set).  Same shape as the first set.
+    size_t alt_offset = 0;         // second set of partial buffers S_0..S_L
+    size_t packed_alt_offset = 0;  // second set of data+flag buffers
+    size_t fused_bytes = 0;        // header + flags + first set of partial buffers: what the flag exchange needs
     size_t scratch_bytes = 0;
 };
 
@@ -55,7 +69,17 @@ struct rar_plan_s {
     long resident[4] = {0, 0, 0, 0};  // cached residency of the fused kernel per unroll 1,2,4,8
     long resident_packed[4] = {0, 0, 0, 0};  // same for the packed fused kernel
     bool have_resident = false;
+    long resident_chain[4] = {0, 0, 0, 0};         // same for the kernels that run a chain of calls
+    long resident_chain_packed[4] = {0, 0, 0, 0};
+    bool have_resident_chain = false;
     int compute_units = 256;   // of the device the residency was measured on (MI355X until then)
+    int device = -1;           // the device of the first launch
+    // One word of pinned host memory that a kernel sets when a step-barrier wait gives up, so that
+    // the next call can refuse to run without synchronising anything.  Allocated at the first
+    // launch by the part of the library that may call HIP, released through `release_host_status`.
+    volatile uint32_t *host_status = nullptr;
+    uint32_t *host_status_dev = nullptr;  // the same word as the device addresses it
+    void (*release_host_status)(volatile uint32_t *) = nullptr;
 };
 
 namespace rar {
@@ -78,9 +102,9 @@ inline size_t chunk_begin(const Geometry &g, int c) {
     return b < g.n ? b : g.n;
 }
 
-// Byte offset of S_l(rank) in the scratch.
-inline size_t partial_offset(const Geometry &g, int level, int rank) {
-    return g.data_offset + (static_cast<size_t>(level) * g.P + rank) * g.chunk_stride;
+// Byte offset of S_l(rank) in the scratch (set 0, or set 1 for the odd calls of a chain).
+inline size_t partial_offset(const Geometry &g, int level, int rank, int set = 0) {
+    return (set ? g.alt_offset : g.data_offset) + (static_cast<size_t>(level) * g.P + rank) * g.chunk_stride;
 }
 
 struct Tuning {
@@ -104,5 +128,10 @@ inline int effective_mode(const rar_plan_t &plan) {
 // Resolve the plan's tuning.  max_resident[i] = workgroups the device can hold at once for
 // the fused kernel with unroll 1 << i (nullptr or 0 = no residency limit, for host-only use).
 Tuning resolve_tuning(const rar_plan_t &plan, const long *max_resident);
+
+// The tuning of a chained launch (rar_allreduce_chain): the plan's tuning, narrowed where needed
+// so that a workgroup has two places of its own in every partial buffer when the plan has no
+// second set of buffers (its trips then alternate between the two places across calls).
+Tuning resolve_chain_tuning(const rar_plan_t &plan, const long *max_resident);
 
 }  // namespace rar

@@ -1,9 +1,9 @@
 """Summarise rocprofv3 CSV output for this library's kernels.
 
 usage:
-  python -m paper_2511_09557_amd.rocprof_summary stats  <dir>                 # --kernel-trace --stats run
-  python -m paper_2511_09557_amd.rocprof_summary pmc    <fetch_dir> <write_dir> [--json out.json --workload c4]
-  python -m paper_2511_09557_amd.rocprof_summary counters <dir> [<dir> ...]   # any --pmc runs: mean per dispatch
+  python3 rocprof_summary.py stats  <dir>                 # --kernel-trace --stats run
+  python3 rocprof_summary.py pmc    <fetch_dir> <write_dir> [--json out.json --workload c4]
+  python3 rocprof_summary.py counters <dir> [<dir> ...]   # any --pmc runs: mean per dispatch
 
 `stats` prints calls / average / total duration per kernel from *kernel_stats.csv (or from
 *kernel_trace.csv if the stats file is absent).  `pmc` reads *counter_collection.csv of a

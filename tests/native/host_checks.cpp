@@ -35,6 +35,16 @@ static void check_shape(int P, int G, size_t n, int dtype) {
     CHECK(g.packed_levels == (g.packed_offset ? g.L + (g.fold ? 1 : 0) : 0));
     CHECK(g.data_offset % 256 == 0);
     CHECK(g.scratch_bytes >= g.data_offset + static_cast<size_t>(g.L + 1) * P * g.chunk_stride);
+    CHECK(g.fused_bytes == g.data_offset + static_cast<size_t>(g.L + 1) * P * g.chunk_stride);
+    // the second set of exchange buffers (odd calls of a chain) exists exactly where the data+flag
+    // buffers do, lies behind them, and has the shape of the first set
+    CHECK((g.alt_offset != 0) == (g.packed_offset != 0) && (g.packed_alt_offset != 0) == (g.packed_offset != 0));
+    if (g.alt_offset) {
+        CHECK(g.alt_offset == g.packed_offset + static_cast<size_t>(g.packed_levels) * P * g.packed_stride);
+        CHECK(g.packed_alt_offset == g.alt_offset + static_cast<size_t>(g.L + 1) * P * g.chunk_stride);
+        CHECK(g.scratch_bytes == g.packed_alt_offset + static_cast<size_t>(g.packed_levels) * P * g.packed_stride);
+        CHECK(g.alt_offset % 256 == 0 && g.packed_alt_offset % 256 == 0);
+    }
     // peers: mutual, same local id; a node that sits out has a partner on the next node that
     // takes part, and nothing reaches past rank P - 1
     for (int p = 0; p < P; ++p) {
@@ -78,6 +88,17 @@ static void check_shape(int P, int G, size_t n, int dtype) {
                 if (resident[0]) {
                     const int idx = t.unroll == 1 ? 0 : t.unroll == 2 ? 1 : t.unroll == 4 ? 2 : 3;
                     CHECK(static_cast<long>(P) * t.B_s <= resident[idx] || t.B_s == 1);
+                }
+                // never more than four workgroups per compute unit (256 units until a device is known)
+                CHECK(static_cast<long>(P) * t.B_s <= 4L * 256 || t.B_s == 1);
+                // a chained launch: the same, and without a second set of buffers two places per
+                // workgroup fit inside one partial buffer
+                const rar::Tuning tc = rar::resolve_chain_tuning(*plan, resident[0] ? resident : nullptr);
+                CHECK(tc.unroll == t.unroll && tc.B_s >= 1 && tc.B_s <= t.B_s && tc.iters >= 1);
+                CHECK(static_cast<size_t>(tc.B_s) * tc.iters * slice >= g.chunk_vecs);
+                if (g.L > 0 && g.alt_offset == 0) {
+                    CHECK(2 * static_cast<size_t>(tc.B_s) * slice * 16 <= g.chunk_stride);
+                    CHECK(tc.iters >= 2);
                 }
             }
     rar_plan_free(plan);

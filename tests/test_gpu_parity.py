@@ -393,7 +393,7 @@ def test_odd_node_count_under_replay():
 
 
 def test_fused_equals_stepwise_under_replay():
-    """Stress of the flag protocol: 1500 fused and packed calls with fresh inputs and changing
+    """Stress of the flag protocol: 10,000 fused and packed calls with fresh inputs and changing
     launch shapes (odd B_s puts the exchanging workgroups on different XCDs), each compared with
     the stepwise path, which synchronises by kernel boundaries only."""
     P, G, n = 32, 4, 256 * 1024
@@ -409,7 +409,7 @@ def test_fused_equals_stepwise_under_replay():
     c.bind([wc[p] for p in range(P)])
     print("[gpu] replay stress", flush=True)
     shapes = [(0, 0), (4, 8192), (3, 4096), (5, 16384), (1, 32768), (16, 4096)]
-    for it in range(1500):
+    for it in range(10000):
         if it % 10 == 0:
             src.copy_(torch.randn(P, n, device="cuda:0", generator=gen))
         else:
@@ -421,6 +421,8 @@ def test_fused_equals_stepwise_under_replay():
         assert torch.equal(wa.view(torch.int16), wb.view(torch.int16)), ("fused", it)
         assert torch.equal(wc.view(torch.int16), wb.view(torch.int16)), ("packed", it)
         assert torch.equal(wb[P - 1].view(torch.int16), wb[0].view(torch.int16)), ("ranks differ", it)
+        if it % 1000 == 999:
+            print(f"[gpu] replay stress: {it + 1} calls", flush=True)
     assert a.status() == 0 and c.status() == 0
     a.close(), b.close(), c.close()
 
@@ -456,6 +458,29 @@ def test_graph_replay(mode):
     ar.close()
 
 
+def force_timeout(ar, bufs, calls=20):
+    """Launch with a 10 ns wait limit until a wait has given up (likely within a few calls, not
+    certain: a wait that is satisfied within 32 polls never looks at the clock).  Every kernel
+    still runs to its end.  Returns whether a time-out was reported; the plan is re-armed."""
+    rar.rar_plan_set_wait_limit_us(ar.plan, 1)
+    seen = False
+    try:
+        for _ in range(calls):
+            try:
+                ar(bufs)
+            except rar.RarError as e:             # the launch itself refuses: the plan is poisoned
+                assert e.status == -8
+                assert ar.status() == -8          # the report re-arms the plan
+                seen = True
+                break
+            if ar.status() == -8:
+                seen = True
+                break
+    finally:
+        rar.rar_plan_set_wait_limit_us(ar.plan, 5_000_000)
+    return seen
+
+
 @pytest.mark.parametrize("mode", ["fused", "packed"])
 def test_wait_limit_ends_every_workgroup(mode):
     """A 1-tick wait limit makes waits give up instead of spinning: the kernel must still
@@ -466,20 +491,105 @@ def test_wait_limit_ends_every_workgroup(mode):
     ar = rar.AllReduce(w.P, w.G, w.n, 0, MODES[mode])
     ar.set_tuning(2, 4096)                     # many trips, so some wait is certain to be pending
     bufs = to_device(x)
-    rar.rar_plan_set_wait_limit_us(ar.plan, 1)
     print("[gpu] wait-limit run", flush=True)
-    timed_out = False
-    for _ in range(20):
-        ar(bufs)
-        if ar.status() == -8:
-            timed_out = True
-            break
-    rar.rar_plan_set_wait_limit_us(ar.plan, 5_000_000)
+    timed_out = force_timeout(ar, bufs)
+    assert ar.status() == 0                    # reported once, then clean
     bufs = to_device(x)
     ar(bufs)
     assert ar.status() == 0
     assert_same_bits(to_host(bufs, x.dtype), want, "after a time-out")
     print(f"[gpu] wait-limit run: time-out seen = {timed_out}", flush=True)   # likely, not certain; recovery is what is checked
+    ar.close()
+
+
+def test_a_timed_out_plan_refuses_to_launch():
+    """After a wait has given up, the plan's flags cannot be trusted: every launch returns
+    RAR_ERR_TIMEOUT and enqueues nothing until rar_plan_status has been asked."""
+    w = ri.WORKLOADS["c3"]
+    x = ri.make_inputs(w)
+    want = oracle.allreduce(x, w.G, threads=8)
+    ar = rar.AllReduce(w.P, w.G, w.n, 0, 1)
+    ar.set_tuning(2, 4096)
+    bufs = to_device(x)
+    ar.bind(bufs)
+    rar.rar_plan_set_wait_limit_us(ar.plan, 1)
+    print("[gpu] poisoned plan", flush=True)
+    refused = False
+    for _ in range(30):
+        try:
+            ar.launch()
+        except rar.RarError as e:
+            assert e.status == -8
+            refused = True
+            break
+        torch.cuda.synchronize()               # the kernel has ended: its report, if any, is in host memory
+    rar.rar_plan_set_wait_limit_us(ar.plan, 5_000_000)
+    if refused:
+        before = [b.clone() for b in bufs]
+        for call in (ar.launch, lambda: ar.launch_chain(2), ar.barrier_only):
+            with pytest.raises(rar.RarError) as e:
+                call()
+            assert e.value.status == -8
+        torch.cuda.synchronize()
+        for b, old in zip(bufs, before):       # nothing was enqueued
+            assert torch.equal(b.view(torch.int16), old.view(torch.int16))
+        assert ar.status() == -8
+    assert ar.status() == 0
+    bufs = to_device(x)
+    ar(bufs)
+    assert ar.status() == 0
+    assert_same_bits(to_host(bufs, x.dtype), want, "after the report")
+    print(f"[gpu] poisoned plan: a launch was refused = {refused}", flush=True)
+    ar.close()
+
+
+def test_autotune_discards_candidates_that_time_out():
+    """rar_autotune with a 10 ns wait limit: candidates during which a wait gave up do not count.
+    Either some candidate survives (then the plan must be clean and exact with the chosen pair),
+    or none does and the call says RAR_ERR_TIMEOUT; the plan works afterwards either way."""
+    w = ri.WORKLOADS["c3"]
+    x = ri.make_inputs(w)
+    want = oracle.allreduce(x, w.G, threads=8)
+    ar = rar.AllReduce(w.P, w.G, w.n, 0, 1)
+    rar.rar_plan_set_wait_limit_us(ar.plan, 1)
+    print("[gpu] autotune under a 10 ns wait limit", flush=True)
+    try:
+        ar.autotune(to_device(x), calls=5)
+        outcome = "a candidate survived"
+    except rar.RarError as e:
+        assert e.status == -8
+        outcome = "no candidate survived"
+    rar.rar_plan_set_wait_limit_us(ar.plan, 5_000_000)
+    assert ar.status() == 0                    # autotune leaves no time-out pending
+    bufs = to_device(x)
+    ar(bufs)
+    assert ar.status() == 0
+    assert_same_bits(to_host(bufs, x.dtype), want, outcome)
+    print(f"[gpu] autotune under a 10 ns wait limit: {outcome}", flush=True)
+    ar.close()
+
+
+def test_first_call_inside_capture_is_refused():
+    """A plan's first launch sets up flags and host memory and cannot be part of a graph."""
+    w = ri.WORKLOADS["c1"]
+    x = ri.make_inputs(w)
+    want = oracle.allreduce(x, w.G, threads=8)
+    ar = rar.AllReduce(w.P, w.G, w.n, 0, 1)
+    bufs = to_device(x)
+    ar.bind(bufs)
+    stream = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    print("[gpu] first call inside capture", flush=True)
+    with torch.cuda.stream(stream):
+        with torch.cuda.graph(graph, stream=stream):
+            with pytest.raises(rar.RarError) as e:
+                ar.launch(stream)
+            assert e.value.status == -10
+    torch.cuda.synchronize()
+    ar.launch()                                # eager: fine, and later captures are too
+    assert ar.status() == 0
+    assert_same_bits(to_host(bufs, x.dtype), want, "eager after the refused capture")
+    ar.close()
 
 
 @pytest.mark.parametrize("mode", ["fused", "auto"])
@@ -515,8 +625,9 @@ def test_two_plans_on_two_streams(name, mode):
 @pytest.mark.parametrize("mode", ["fused", "packed"])
 def test_compute_on_another_stream_at_the_same_time(mode):
     """Matrix products on a second stream compete for the compute units while the all-reduce runs,
-    so its workgroups are not all resident at once.  The step waits must still end: either the call
-    completes with the oracle's bits or, at worst, it reports a time-out; it never hangs."""
+    so its workgroups are not all resident at once.  The step waits must still end: every call that
+    reports no time-out has the oracle's bits, and a call that does report one is followed by a
+    clean call on the same plan; it never hangs."""
     w = ri.WORKLOADS["c3"]
     x = ri.make_inputs(w)
     want = oracle.allreduce(x, w.G, threads=8)
@@ -540,6 +651,11 @@ def test_compute_on_another_stream_at_the_same_time(mode):
         if status == 0:
             assert_same_bits(to_host(bufs, x.dtype), want, f"{mode} rep {rep}")
             ok += 1
+        else:                                      # the device is idle now: the plan must recover at once
+            bufs = to_device(x)
+            ar(bufs)
+            assert ar.status() == 0
+            assert_same_bits(to_host(bufs, x.dtype), want, f"{mode} rep {rep}, call after the time-out")
     print(f"[gpu] concurrent compute {mode}: {ok} of 5 calls completed", flush=True)
     assert ok >= 1
     ar.close()
@@ -568,3 +684,72 @@ def test_allreduce_rejects_bad_arguments():
     rar.rar_allreduce(ptrs, plan)
     torch.cuda.synchronize()
     rar.rar_plan_free(plan)
+
+
+@pytest.mark.parametrize("mode", ["fused", "auto"])
+@pytest.mark.parametrize("name", ["c2", "c4"])
+def test_two_default_plans_on_two_streams(name, mode):
+    """Two plans that were told nothing about each other, launched back to back on two streams: the
+    library orders the second fused kernel after the first (an event between the streams), so both
+    complete with the oracle's bits and no wait times out."""
+    w = ri.WORKLOADS[name]
+    xa = ri.make_inputs(w)
+    xb = np.ascontiguousarray(xa[::-1])
+    want_a, want_b = oracle.allreduce(xa, w.G, threads=8), oracle.allreduce(xb, w.G, threads=8)
+    a = rar.AllReduce(w.P, w.G, w.n, 0, MODES[mode])
+    b = rar.AllReduce(w.P, w.G, w.n, 0, MODES[mode])
+    for p in (a, b):
+        rar.rar_plan_set_wait_limit_us(p.plan, 2_000_000)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    for rep in range(3):
+        ba, bb = to_device(xa), to_device(xb)
+        a.bind(ba), b.bind(bb)
+        torch.cuda.synchronize()
+        print(f"[gpu] two default plans {name} {mode} rep {rep}", flush=True)
+        for _ in range(1 + 9 * (rep == 2)):        # the last repetition: ten alternating pairs in a row
+            a.launch(s1)
+            b.launch(s2)
+        torch.cuda.synchronize()
+        assert a.status(s1) == 0 and b.status(s2) == 0
+        if rep < 2:
+            assert_same_bits(to_host(ba, xa.dtype), want_a, "plan a")
+            assert_same_bits(to_host(bb, xb.dtype), want_b, "plan b")
+    a.close(), b.close()
+
+
+def test_measurement_aids():
+    """rar_launch_floor, rar_barrier_only, rar_copy_probe and rar_read_probe do what the header says
+    and leave the plan usable: the barrier-only kernel moves the flag counters like a real call."""
+    w = ri.WORKLOADS["c2"]
+    x = ri.make_inputs(w)
+    want = oracle.allreduce(x, w.G, threads=8)
+    ar = rar.AllReduce(w.P, w.G, w.n, 0, 1)
+    bufs = to_device(x)
+    ar.bind(bufs)
+    print("[gpu] measurement aids", flush=True)
+    ar.launch_floor()
+    for B_s, C_s in ((0, 0), (3, 4096), (16, 8192)):
+        ar.set_tuning(B_s, C_s)
+        ar.barrier_only()
+        ar.launch_floor()
+    assert ar.status() == 0
+    assert_same_bits(to_host(bufs, x.dtype), x, "the aids move no data")
+    ar.set_tuning(0, 0)
+    ar.launch()
+    assert ar.status() == 0
+    assert_same_bits(to_host(bufs, x.dtype), want, "a real call after barrier-only calls")
+    ar.close()
+    src = torch.randint(0, 255, (1 << 20,), dtype=torch.uint8, device="cuda:0")
+    dst = torch.zeros_like(src)
+    sink = torch.zeros(16, dtype=torch.uint8, device="cuda:0")
+    st = torch.cuda.current_stream().cuda_stream
+    rar.rar_copy_probe(dst.data_ptr(), src.data_ptr(), src.numel(), st)
+    rar.rar_read_probe(sink.data_ptr(), src.data_ptr(), src.numel(), st)
+    torch.cuda.synchronize()
+    assert torch.equal(dst, src)
+    with pytest.raises(rar.RarError):
+        rar.rar_copy_probe(dst.data_ptr() + 8, src.data_ptr(), 1024, st)
+    with pytest.raises(rar.RarError):
+        rar.rar_read_probe(sink.data_ptr(), src.data_ptr(), 1000, st)
+    rar.rar_read_probe(sink.data_ptr(), src.data_ptr(), 0, st)
+    torch.cuda.synchronize()

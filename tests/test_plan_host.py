@@ -23,7 +23,7 @@ def test_every_declared_symbol_is_exported():
 
 def test_version_and_strerror():
     assert rar.rar_version() >= 100
-    for code in range(0, -10, -1):
+    for code in range(0, -11, -1):
         assert rar.rar_strerror(code) != "unknown status"
     assert rar.rar_strerror(-99) == "unknown status"
 
