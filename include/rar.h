@@ -232,6 +232,21 @@ int rar_allreduce(void *const *bufs, rar_plan_t *plan, void *stream);
  * Runs the plan's fused mode (flag or data+flag exchange); RAR_MODE_STEPWISE: RAR_ERR_ARG. */
 int rar_allreduce_chain(void *const *bufs, rar_plan_t *plan, int K, void *stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): rar_allreduce in RAR_MODE_FUSED (flag exchange) on
+ * a scratch array that is part of the library (RAR_STATIC_SCRATCH_BYTES of device memory per
+ * GPU, held until the process ends) instead of the plan's lent scratch, which need not be
+ * set.  Allocates nothing, neither on the device nor on the host.  The plan's flag-exchange
+ * footprint (header, flags, partial buffers: rar_plan_static_bytes) must fit the array:
+ * RAR_ERR_LIMIT otherwise.  All calls on one GPU share the array: the call clears the header
+ * and the flags with a fill kernel on `stream` before the all-reduce, so plans of any shape
+ * may alternate, and calls that overlap in time on one GPU race (order them on one stream).
+ * A wait that gives up is reported by the plan's next rar_plan_status (it reads the array's
+ * header); since every call clears the flags, it does not affect later calls. */
+#define RAR_STATIC_SCRATCH_BYTES (48u << 20)
+int rar_allreduce_static(void *const *bufs, rar_plan_t *plan, void *stream);
+size_t rar_plan_static_bytes(const rar_plan_t *plan);
+
 /* Pick B_s and C_s by measurement (the paper tunes both once per message size and node count,
  * Section 4.2.1, and leaves heuristics to future work).  Runs the fused all-reduce of the
  * plan's current mode on `bufs` (same contract as rar_allreduce; the buffers are overwritten

@@ -63,6 +63,8 @@ def _load() -> ctypes.CDLL:
         "rar_step_combine": (ci, [vp, vp, sz, sz, ci, vp]),
         "rar_allreduce": (ci, [ctypes.POINTER(vp), vp, vp]),
         "rar_allreduce_chain": (ci, [ctypes.POINTER(vp), vp, ci, vp]),
+        "rar_allreduce_static": (ci, [ctypes.POINTER(vp), vp, vp]),
+        "rar_plan_static_bytes": (sz, [vp]),
         "rar_autotune": (ci, [ctypes.POINTER(vp), vp, vp, ci, ctypes.POINTER(ctypes.c_double)]),
         "rar_launch_floor": (ci, [vp, vp]),
         "rar_barrier_only": (ci, [vp, vp]),
@@ -81,7 +83,7 @@ EXPORTS = ["rar_version", "rar_strerror", "rar_last_hip_error", "rar_plan", "rar
            "rar_plan_scratch_bytes", "rar_plan_scratch_layout", "rar_plan_set_scratch", "rar_plan_set_mode",
            "rar_plan_get_mode", "rar_plan_effective_mode", "rar_plan_set_tuning", "rar_plan_get_tuning",
            "rar_plan_set_concurrency", "rar_plan_set_wait_limit_us", "rar_plan_status", "rar_step_combine", "rar_allreduce",
-           "rar_allreduce_chain", "rar_autotune", "rar_launch_floor", "rar_barrier_only", "rar_copy_probe", "rar_read_probe"]
+           "rar_allreduce_chain", "rar_allreduce_static", "rar_plan_static_bytes", "rar_autotune", "rar_launch_floor", "rar_barrier_only", "rar_copy_probe", "rar_read_probe"]
 
 
 def _check(status: int, where: str) -> int:
@@ -200,6 +202,19 @@ def rar_allreduce(buf_ptrs: Sequence[int], plan: int, stream: int = 0) -> None:
 def rar_allreduce_chain(buf_ptrs: Sequence[int], plan: int, K: int, stream: int = 0) -> None:
     arr = (ctypes.c_void_p * len(buf_ptrs))(*buf_ptrs)
     _check(lib.rar_allreduce_chain(arr, plan, K, stream), "rar_allreduce_chain")
+
+
+RAR_STATIC_SCRATCH_BYTES = 48 << 20
+
+
+def rar_allreduce_static(buf_ptrs: Sequence[int], plan: int, stream: int = 0) -> None:
+    """rar_allreduce on the library's own scratch array (the plan needs no scratch of its own)."""
+    arr = (ctypes.c_void_p * len(buf_ptrs))(*buf_ptrs)
+    _check(lib.rar_allreduce_static(arr, plan, stream), "rar_allreduce_static")
+
+
+def rar_plan_static_bytes(plan: int) -> int:
+    return lib.rar_plan_static_bytes(plan)
 
 
 def rar_autotune(buf_ptrs: Sequence[int], plan: int, stream: int = 0, calls: int = 20) -> float:

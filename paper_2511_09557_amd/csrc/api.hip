@@ -11,7 +11,30 @@ using rar::Geometry;
 using rar::RankPtrs;
 using rar::Tuning;
 
+// The scratch of rar_allreduce_static: part of the library's image on every GPU it runs on, so a
+// caller that cannot allocate has somewhere to exchange partials.  Host code never uses this name
+// as an address: static_scratch() below asks the runtime where the array lives on the current
+// device and everything else goes through that pointer.
+static __device__ __align__(256) unsigned char scratch[RAR_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+std::mutex g_static_guard;
+unsigned char *g_static_ptr[16];   // device address of `scratch` per device (each GPU has its own copy)
+
+int static_scratch(int *device, unsigned char **out) {
+    int dev = 0;
+    if (rar::note_hip(hipGetDevice(&dev)) != hipSuccess || dev < 0 || dev >= 16) return RAR_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_static_guard);
+    if (!g_static_ptr[dev]) {
+        void *ptr = nullptr;
+        if (rar::note_hip(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch))) != hipSuccess || !ptr) return RAR_ERR_HIP;
+        g_static_ptr[dev] = static_cast<unsigned char *>(ptr);
+    }
+    if (device) *device = dev;
+    *out = g_static_ptr[dev];
+    return RAR_OK;
+}
 
 inline hipStream_t as_stream(void *s) { return static_cast<hipStream_t>(s); }
 
@@ -39,10 +62,10 @@ int ensure_ordering_event(int device);
 // A step-barrier wait of this plan has given up and rar_plan_status has not been asked since.
 inline bool poisoned(const rar_plan_t *plan) { return plan->host_status && *plan->host_status != 0u; }
 
-// First launch of a plan: remember the device, ask how many workgroups of each fused kernel it
-// holds at once, and allocate the pinned word through which a kernel reports a time-out.
-int ensure_residency(rar_plan_t *plan) {
-    if (plan->have_resident) return RAR_OK;
+// Remember the device and ask how many workgroups of each fused kernel it holds at once.
+// Allocates nothing.
+int ensure_occupancy(rar_plan_t *plan) {
+    if (plan->have_occupancy) return RAR_OK;
     rar::DeviceInfo info;
     int got = rar::device_info(&info);
     if (got != RAR_OK) return got;
@@ -54,7 +77,17 @@ int ensure_residency(rar_plan_t *plan) {
         rc = rar::fused_max_resident(plan->geo.dtype, plan->geo.G, 1 << i, true, plan->geo.fold != 0, false, &plan->resident_packed[i]);
         if (rc != RAR_OK) return rc;
     }
-    int rc = ensure_ordering_event(plan->device);
+    plan->have_occupancy = true;
+    return RAR_OK;
+}
+
+// First launch of a plan on its own scratch: the above, plus the pinned word through which a
+// kernel reports a time-out and the device's event for ordering launches of different streams.
+int ensure_residency(rar_plan_t *plan) {
+    if (plan->have_resident) return RAR_OK;
+    int rc = ensure_occupancy(plan);
+    if (rc != RAR_OK) return rc;
+    rc = ensure_ordering_event(plan->device);
     if (rc != RAR_OK) return rc;
     if (!plan->host_status) {
         void *word = nullptr;
@@ -222,6 +255,19 @@ int rar_plan_status(rar_plan_t *plan, void *stream) {
         if (rar::note_hip(hipMemcpy(&word, plan->scratch, sizeof word, hipMemcpyDeviceToHost)) != hipSuccess) return RAR_ERR_HIP;
         timed_out = timed_out || word != 0;
     }
+    if (plan->ran_static) {  // calls on the library's array report through its header alone
+        unsigned char *array = nullptr;
+        int rc = static_scratch(nullptr, &array);
+        if (rc != RAR_OK) return rc;
+        uint32_t word = 0;
+        if (rar::note_hip(hipMemcpy(&word, array, sizeof word, hipMemcpyDeviceToHost)) != hipSuccess) return RAR_ERR_HIP;
+        if (word != 0) {
+            timed_out = true;
+            word = 0;
+            if (rar::note_hip(hipMemcpy(array, &word, sizeof word, hipMemcpyHostToDevice)) != hipSuccess) return RAR_ERR_HIP;
+        }
+        plan->ran_static = false;
+    }
     if (!timed_out) return RAR_OK;
     rearm(plan);  // counters of different slots may now disagree: start over
     return RAR_ERR_TIMEOUT;
@@ -294,6 +340,32 @@ int rar_allreduce_chain(void *const *bufs, rar_plan_t *plan, int K, void *stream
     order_fused_launch(plan, st);
     if (!packed) return rar::launch_fused(*plan, plan->scratch, ptrs, t, true, K, st);
     return rar::launch_fused_packed(*plan, ptrs, t, K, st);
+}
+
+int rar_allreduce_static(void *const *bufs, rar_plan_t *plan, void *stream) {
+    if (!bufs || !plan) return RAR_ERR_ARG;
+    const Geometry &g = plan->geo;
+    if (g.fused_bytes > RAR_STATIC_SCRATCH_BYTES) return RAR_ERR_LIMIT;
+    RankPtrs ptrs;
+    int rc = check_bufs(bufs, g, &ptrs);
+    if (rc != RAR_OK) return rc;
+    unsigned char *array = nullptr;
+    int device = 0;
+    rc = static_scratch(&device, &array);
+    if (rc != RAR_OK) return rc;
+    rc = ensure_occupancy(plan);
+    if (rc != RAR_OK) return rc;
+    if (plan->device != device) return RAR_ERR_ARG;  // the plan belongs to another device
+    Tuning t;
+    rc = fused_tuning(plan, false, &t);
+    if (rc != RAR_OK) return rc;
+    hipStream_t st = as_stream(stream);
+    // whatever the last call on this GPU left behind: header and flags start at zero (a fill
+    // kernel, which a captured graph can replay; no pointer to host memory in the header)
+    rc = rar::launch_fill_zero(array, g.data_offset, nullptr, st);
+    if (rc != RAR_OK) return rc;
+    plan->ran_static = true;
+    return rar::launch_fused(*plan, array, ptrs, t, true, 0, st);
 }
 
 int rar_autotune(void *const *bufs, rar_plan_t *plan, void *stream, int calls, double *best_us) {

@@ -220,6 +220,8 @@ int rar_plan_chunk(const rar_plan_t *plan, int c, size_t *offset, size_t *length
 
 size_t rar_plan_scratch_bytes(const rar_plan_t *plan) { return plan ? plan->geo.scratch_bytes : 0; }
 
+size_t rar_plan_static_bytes(const rar_plan_t *plan) { return plan ? plan->geo.fused_bytes : 0; }
+
 int rar_plan_scratch_layout(const rar_plan_t *plan, size_t *flags_offset, size_t *flags_bytes,
                             size_t *packed_offset, size_t *packed_bytes) {
     if (!plan) return RAR_ERR_ARG;
@@ -268,7 +270,7 @@ int rar_plan_set_tuning(rar_plan_t *plan, int B_s, size_t C_s) {
 
 int rar_plan_get_tuning(const rar_plan_t *plan, int *B_s, size_t *C_s) {
     if (!plan || !B_s || !C_s) return RAR_ERR_ARG;
-    const long *resident = !plan->have_resident ? nullptr
+    const long *resident = !plan->have_occupancy ? nullptr
                            : rar::effective_mode(*plan) == RAR_MODE_FUSED_PACKED ? plan->resident_packed : plan->resident;
     rar::Tuning t = rar::resolve_tuning(*plan, resident);
     *B_s = t.B_s;

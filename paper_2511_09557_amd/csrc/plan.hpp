@@ -68,12 +68,14 @@ struct rar_plan_s {
     bool packed_clean = false; // data+flag buffers zeroed (no stale word can match a sequence number)
     long resident[4] = {0, 0, 0, 0};  // cached residency of the fused kernel per unroll 1,2,4,8
     long resident_packed[4] = {0, 0, 0, 0};  // same for the packed fused kernel
-    bool have_resident = false;
+    bool have_occupancy = false;   // the four figures above are known
+    bool have_resident = false;    // ... and the plan's host-side set-up (time-out word, ordering event) is done
     long resident_chain[4] = {0, 0, 0, 0};         // same for the kernels that run a chain of calls
     long resident_chain_packed[4] = {0, 0, 0, 0};
     bool have_resident_chain = false;
     int compute_units = 256;   // of the device the residency was measured on (MI355X until then)
     int device = -1;           // the device of the first launch
+    bool ran_static = false;   // rar_allreduce_static has run on this plan (its time-outs sit in the library's array)
     // One word of pinned host memory that a kernel sets when a step-barrier wait gives up, so that
     // the next call can refuse to run without synchronising anything.  Allocated at the first
     // launch by the part of the library that may call HIP, released through `release_host_status`.
