@@ -174,8 +174,35 @@ def cold_leg(ar, stream_calls: int = 20, replays: int = 5):
         ar.launch(st)
     alone = min(time_graph(sweep_caches, stream_calls, 1, replays) for _ in range(2))
     pair = min(time_graph(both, stream_calls, 1, replays) for _ in range(2))
-    del src, dst
-    return pair - alone, alone
+    # the all-reduce alone between two events, launched eagerly right behind the copy (its launch
+    # is queued while the copy runs): the kernel's own duration plus the gap before it
+    cur = torch.cuda.current_stream()
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(40)]
+    for e0, e1 in pairs:
+        sweep_caches(cur)
+        e0.record()
+        ar.launch(cur.cuda_stream)
+        e1.record()
+    torch.cuda.synchronize()
+    bracketed = sorted(e0.elapsed_time(e1) * 1000.0 for e0, e1 in pairs[5:])
+    bracketed_us = bracketed[len(bracketed) // 2]
+    del dst
+    # the same with a sweep that only reads (512 MiB): the caches then hold clean lines of other
+    # data, where the copy above leaves 256 MiB of modified lines that have to be written back
+    # while the all-reduce runs
+    big = torch.full((2 * COPY_PROBE_BYTES,), 7, dtype=torch.uint8, device="cuda:0")
+    sink = torch.zeros(16, dtype=torch.uint8, device="cuda:0")
+
+    def sweep_reading(st):
+        rar.rar_read_probe(sink.data_ptr(), big.data_ptr(), 2 * COPY_PROBE_BYTES, st.cuda_stream)
+
+    def both_reading(st):
+        sweep_reading(st)
+        ar.launch(st)
+    alone_r = min(time_graph(sweep_reading, stream_calls, 1, replays) for _ in range(2))
+    pair_r = min(time_graph(both_reading, stream_calls, 1, replays) for _ in range(2))
+    del src, big
+    return pair - alone, alone, pair_r - alone_r, bracketed_us
 
 
 def bench_chain(ar, K: int = 100, launches: int = 10):
@@ -271,9 +298,11 @@ def bench_workload(name: str, warmup: int, steps: int, extras: bool, mode: str =
         # k+1 as soon as its own slices of call k are gathered; per-call time
         out["chain100_us"] = bench_chain(ar)
         # the memory-side cache swept before every call (256 MiB copy in between, copy time subtracted)
-        cold, sweep_us = cold_leg(ar)
+        cold, sweep_us, cold_clean, cold_events = cold_leg(ar)
         out["cold_us"] = cold
+        out["cold_between_events_us"] = cold_events
         out["cold_sweep_copy_us"] = sweep_us
+        out["cold_after_read_sweep_us"] = cold_clean
         # back-to-back calls versus calls with compute in between (the paper's Appendix B runs a
         # synthetic matmul between all-reduces).  The compute here is what precedes the all-reduce
         # in a tensor-parallel layer: every rank's row-parallel product, tokens x hidden/P @
@@ -620,6 +649,22 @@ def cold_loop(workload: str, calls: int) -> None:
     ar.close()
 
 
+def chain_loop(workload: str, launches: int, K: int = 100) -> None:
+    """For a profiler: `launches` chained launches of K all-reduces each (rar_allreduce_chain), fused mode."""
+    import torch
+    import paper_2511_09557_amd as rar
+    import rar_inputs as ri
+    w = ri.WORKLOADS[workload]
+    bufs = device_bufs(ri.make_inputs(w))
+    ar = rar.AllReduce(w.P, w.G, w.n, rar.RAR_BF16, rar.RAR_MODE_AUTO)
+    ar.bind(bufs)
+    st = torch.cuda.current_stream().cuda_stream
+    for _ in range(launches):
+        ar.launch_chain(K, st)
+    assert ar.status() == 0
+    ar.close()
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -631,6 +676,7 @@ def main() -> int:
                     help="with --no-extras: run the headline workload in this mode (the JSON line says which)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--cold-loop", type=int, metavar="CALLS", help="for a profiler: only CALLS x (cache sweep, fused all-reduce of --workload)")
+    ap.add_argument("--chain-loop", type=int, metavar="LAUNCHES", help="for a profiler: only LAUNCHES chains of 100 all-reduces of --workload (automatic mode)")
     ap.add_argument("--sensitivity", metavar="OUT.md", help="run the B_s x C_s sensitivity study instead and write it to this file")
     ap.add_argument("--hierarchy", metavar="OUT.md", help="run the flat-versus-hierarchical study instead and write it to this file")
     ap.add_argument("--sweep", metavar="OUT.jsonl", help="run the message-size sweep instead and write it to this file")
@@ -661,6 +707,9 @@ def main() -> int:
         cold_loop(args.workload, args.cold_loop)
         copy_probe()
         return 0
+    if args.chain_loop:
+        chain_loop(args.workload, args.chain_loop)
+        return 0
 
     if args.mode != "fused" and not args.no_extras:
         print("bench.py: --mode needs --no-extras", file=sys.stderr)
@@ -687,11 +736,20 @@ def main() -> int:
                 "traffic_GBps": (traffic / (us * 1e-6) / 1e9) if traffic else None,
                 "traffic_frac": (traffic / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS) if traffic else None}
     if not args.no_extras:
-        cold = head["cold_us"]
+        # the kernel's duration with the memory-side cache and the L2s swept before every call
+        cold = head["cold_between_events_us"]
+        diff = head["cold_us"]
         roofline["cold"] = {"us": cold, "GBps": moved / (cold * 1e-6) / 1e9, "frac": moved / (cold * 1e-6) / 1e9 / HBM_PEAK_GBPS,
                             "traffic_GBps": (traffic / (cold * 1e-6) / 1e9) if traffic else None,
-                            "method": "HIP graphs of 20 x (256 MiB copy, all-reduce) minus graphs of the copies alone: "
-                                      "the memory-side cache and the L2s are swept before every call"}
+                            "method": "a 256 MiB copy before every all-reduce; median of 35 eager (copy, all-reduce) pairs, HIP "
+                                      "events around the all-reduce alone (the kernel's duration plus the gap before it)",
+                            # what the pair costs beyond the copy: also charges the all-reduce for what it
+                            # leaves the next copy to clean up
+                            "graph_difference_us": diff,
+                            "graph_difference_frac": moved / (diff * 1e-6) / 1e9 / HBM_PEAK_GBPS,
+                            "graph_difference_method": "HIP graphs of 20 x (256 MiB copy, all-reduce) minus graphs of the copies alone",
+                            "after_read_only_sweep_us": head["cold_after_read_sweep_us"],
+                            "after_read_only_sweep_note": "graph difference with a 512 MiB read-only sweep instead of the copy"}
         roofline["streaming_ceilings"] = streaming_ceilings()
     line = {
         "metric": "us per all-reduce at 128KB-2MB bf16 (P virtual ranks); achieved HBM GB/s vs peak",

@@ -1,6 +1,8 @@
 /* Plain C user of the C ABI: no Python, no torch.  Allocates P rank buffers and the scratch with
- * hipMalloc, runs rar_allreduce in every mode and compares the bytes with the CPU oracle
- * (nvrar_oracle_allreduce, linked from oracle/).  Exit status 0 = bit-exact everywhere.
+ * hipMalloc, runs rar_allreduce in every mode and rar_allreduce_chain (two calls in one launch,
+ * against the oracle applied twice) and compares the bytes with the CPU oracle
+ * (nvrar_oracle_allreduce, linked from oracle/).
+ * Exit status 0 = bit-exact everywhere.
  * usage: c_abi_parity P G n dtype(0 bf16 | 1 f32) */
 #include <hip/hip_runtime_api.h>
 #include <stdint.h>
@@ -66,6 +68,23 @@ int main(int argc, char **argv) {
             if (memcmp(host_got, host_want[p], bytes) != 0) { ++failures; fprintf(stderr, "mode %d rank %d differs\n", mode, p); break; }
         }
     }
+    /* two chained calls in one launch = the oracle applied to its own result */
+    void **host_twice = calloc((size_t)P, sizeof *host_twice);
+    for (int p = 0; p < P; ++p) host_twice[p] = malloc(bytes);
+    if (nvrar_oracle_allreduce((const void *const *)host_want, host_twice, G, P / G, n, dtype, 4) != 0) return 4;
+    for (int mode = RAR_MODE_FUSED; mode <= RAR_MODE_FUSED_PACKED; ++mode) {
+        if (rar_plan_set_mode(plan, mode) != RAR_OK) continue;
+        for (int p = 0; p < P; ++p) HIP_OK(hipMemcpy(dev[p], host_in[p], bytes, hipMemcpyHostToDevice));
+        printf("mode %d: chain of 2\n", mode); fflush(stdout);
+        RAR_CHECK(rar_allreduce_chain(dev, plan, 2, NULL));
+        RAR_CHECK(rar_plan_status(plan, NULL));
+        for (int p = 0; p < P; ++p) {
+            HIP_OK(hipMemcpy(host_got, dev[p], bytes, hipMemcpyDeviceToHost));
+            if (memcmp(host_got, host_twice[p], bytes) != 0) { ++failures; fprintf(stderr, "chain, mode %d rank %d differs\n", mode, p); break; }
+        }
+    }
+    for (int p = 0; p < P; ++p) free(host_twice[p]);
+    free(host_twice);
     for (int p = 0; p < P; ++p) { (void)hipFree(dev[p]); free(host_in[p]); free(host_want[p]); }
     (void)hipFree(scratch);
     RAR_CHECK(rar_plan_free(plan));
