@@ -388,6 +388,7 @@ def sweep(path: str) -> None:
                     ar = rar.AllReduce(P, G, n, code, rar.RAR_MODE_FUSED)
                     ar.bind(bufs)
                     alg = algorithmic_bytes(P, G, P // G, nbytes)
+                    mov = moved_bytes(P, G, P // G, nbytes)
                     reps = max(5, min(500, int(2e-2 / max(alg / 5e12, 5e-6))))
                     _, ev = time_calls(lambda: ar.launch(), max(reps // 5, 2), reps)
                     fused = ev * 1000.0 / reps
@@ -409,8 +410,9 @@ def sweep(path: str) -> None:
                     ar.close()
                     row = {"dtype": dtype, "P": P, "G": G, "bytes_per_rank": nbytes, "fused_us": fused,
                            "fused_in_graph_us": graph, "packed_in_graph_us": packed_graph, "auto_mode": auto,
-                           "stepwise_us": stepwise, "algorithmic_bytes": alg,
-                           "fused_GBps": alg / (fused * 1e-6) / 1e9, "B_s": B_s, "C_s": C_s}
+                           "stepwise_us": stepwise, "algorithmic_bytes": alg, "moved_bytes": mov,
+                           "fused_GBps": mov / (fused * 1e-6) / 1e9, "schedule_GBps": alg / (fused * 1e-6) / 1e9,
+                           "B_s": B_s, "C_s": C_s}
                     f.write(json.dumps(row) + "\n")
                     f.flush()
                     rows.append(row)
@@ -423,20 +425,22 @@ def sweep(path: str) -> None:
     with open(md, "w") as f:
         f.write("# Message-size sweep of the all-reduce on one MI355X\n\n"
                 "command: `python3 bench.py --sweep <file>.jsonl`; eager launches timed with HIP events; values N(0,1)\n"
-                "drawn on the device; GB/s = algorithmic bytes `P*(2M + (3L+2)M/G)` / time; `graph` = the call inside a\n"
-                "HIP graph of 20 calls (fused: messages up to 4 MiB; data+flag mode: up to 1 MiB), which takes the host's\n"
-                "launch rate out; `auto` = the mode a plan runs in when none is set.\n")
+                "drawn on the device; GB/s = bytes the fused kernel must move, `P*(2M + 2L*M/G)`, / time, and its fraction of\n"
+                "the 8 TB/s HBM peak (small messages live in the caches: the fraction then says nothing about HBM);\n"
+                "`schedule GB/s` = the schedule's own count with every partial materialised, `P*(2M + (3L+2)M/G)`, / time;\n"
+                "`graph` = the call inside a HIP graph of 20 calls (fused: messages up to 4 MiB; data+flag mode: up to 1 MiB),\n"
+                "which takes the host's launch rate out; `auto` = the mode a plan runs in when none is set.\n")
         key = None
         for r in rows:
             if (r["dtype"], r["P"], r["G"]) != key:
                 key = (r["dtype"], r["P"], r["G"])
                 f.write(f"\n## {r['dtype']}, P={r['P']} (G={r['G']}, N={r['P'] // r['G']})\n\n"
-                        "| bytes per rank | fused us | fused GB/s | frac of 8 TB/s | fused in graph us | data+flag in graph us | auto | stepwise us | B_s | C_s |\n"
-                        "|---|---|---|---|---|---|---|---|---|---|\n")
+                        "| bytes per rank | fused us | GB/s | frac of 8 TB/s | schedule GB/s | fused in graph us | data+flag in graph us | auto | stepwise us | B_s | C_s |\n"
+                        "|---|---|---|---|---|---|---|---|---|---|---|\n")
             g = "-" if r["fused_in_graph_us"] is None else f"{r['fused_in_graph_us']:.2f}"
             pg = "-" if r["packed_in_graph_us"] is None else f"{r['packed_in_graph_us']:.2f}"
             f.write(f"| {r['bytes_per_rank']} | {r['fused_us']:.2f} | {r['fused_GBps']:.0f} | {r['fused_GBps'] / HBM_PEAK_GBPS:.3f} "
-                    f"| {g} | {pg} | {r['auto_mode']} | {r['stepwise_us']:.2f} | {r['B_s']} | {r['C_s']} |\n")
+                    f"| {r['schedule_GBps']:.0f} | {g} | {pg} | {r['auto_mode']} | {r['stepwise_us']:.2f} | {r['B_s']} | {r['C_s']} |\n")
 
 
 def sensitivity(path: str) -> None:
@@ -500,13 +504,14 @@ def hierarchy(path: str) -> None:
     gen.manual_seed(SWEEP_SEED + 99)
     lines = ["# Flat versus hierarchical split of the same ranks, one MI355X (bf16)", "",
              "command: `python3 bench.py --hierarchy <this file>`; fused mode, microseconds per all-reduce inside",
-             "HIP graphs of 100 calls; L = log2 N inter-node steps; algorithmic bytes = P*(2M + (3L+2)M/G).", ""]
+             "HIP graphs of 100 calls; L = log2 N inter-node steps; schedule bytes = P*(2M + (3L+2)M/G) (every partial",
+             "materialised, as it would cross a network); the fused kernel moves P*(2M + 2L*M/G).", ""]
     for P, nbytes in ((16, 256 << 10), (16, 2 << 20), (64, 256 << 10), (64, 2 << 20)):
         n = nbytes // 2
         whole = torch.randn(P, n, device="cuda:0", generator=gen).to(torch.bfloat16)
         bufs = [whole[p] for p in range(P)]
         lines += [f"## P = {P}, {nbytes >> 10} KiB per rank", "",
-                  "| G | N | L | bytes per step and rank | algorithmic MB | us per all-reduce | algorithmic GB/s |", "|---|---|---|---|---|---|---|"]
+                  "| G | N | L | bytes per step and rank | schedule MB | moved MB | us per all-reduce | moved GB/s |", "|---|---|---|---|---|---|---|---|"]
         G = 1
         while G <= P:
             N = P // G
@@ -516,7 +521,8 @@ def hierarchy(path: str) -> None:
             assert ar.status() == 0
             ar.close()
             alg = algorithmic_bytes(P, G, N, nbytes)
-            lines.append(f"| {G} | {N} | {N.bit_length() - 1} | {nbytes // G} | {alg / 1e6:.1f} | {us:.2f} | {alg / us / 1e3:.0f} |")
+            mov = moved_bytes(P, G, N, nbytes)
+            lines.append(f"| {G} | {N} | {N.bit_length() - 1} | {nbytes // G} | {alg / 1e6:.1f} | {mov / 1e6:.1f} | {us:.2f} | {mov / us / 1e3:.0f} |")
             G *= 2
         lines.append("")
         print(f"P={P} {nbytes} B done", file=sys.stderr, flush=True)
