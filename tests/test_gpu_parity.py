@@ -717,6 +717,45 @@ def test_two_default_plans_on_two_streams(name, mode):
     a.close(), b.close()
 
 
+def test_two_default_plans_in_one_graph():
+    """Two plans with the default concurrency on two streams of ONE capture (the second stream forked
+    from the first): the library's ordering becomes edges of the graph, the two chains run one
+    kernel at a time, and every replay gives the oracle's bits."""
+    w = ri.WORKLOADS["c2"]
+    xa = ri.to_bf16_bits(ri.bf16_bits_to_f32(ri.make_inputs(w)) / 64.0)
+    xb = np.ascontiguousarray(xa[::-1])
+    want_a, want_b = xa, xb
+    for _ in range(3):
+        want_a, want_b = oracle.allreduce(want_a, w.G, threads=8), oracle.allreduce(want_b, w.G, threads=8)
+    a = rar.AllReduce(w.P, w.G, w.n, 0, 1)
+    b = rar.AllReduce(w.P, w.G, w.n, 0, 1)
+    sa, sb = to_device(xa), to_device(xb)
+    ba, bb = [t.clone() for t in sa], [t.clone() for t in sb]
+    a.bind(ba), b.bind(bb)
+    a.launch(), b.launch()                       # eager first: set-up stays out of the graph
+    torch.cuda.synchronize()
+    main, side = torch.cuda.Stream(), torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    print("[gpu] two default plans in one graph", flush=True)
+    with torch.cuda.stream(main):
+        with torch.cuda.graph(graph, stream=main):
+            side.wait_stream(main)
+            for _ in range(3):
+                a.launch(main)
+                b.launch(side)
+            main.wait_stream(side)
+    for rep in range(3):
+        for t, s_ in zip(ba + bb, sa + sb):
+            t.copy_(s_)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert a.status() == 0 and b.status() == 0
+        assert_same_bits(to_host(ba, xa.dtype), want_a, f"plan a, replay {rep}")
+        assert_same_bits(to_host(bb, xb.dtype), want_b, f"plan b, replay {rep}")
+    a.close(), b.close()
+
+
 def test_measurement_aids():
     """rar_launch_floor, rar_barrier_only, rar_copy_probe and rar_read_probe do what the header says
     and leave the plan usable: the barrier-only kernel moves the flag counters like a real call."""

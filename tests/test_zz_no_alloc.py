@@ -58,6 +58,38 @@ def test_static_scratch_calls_in_a_row():
         assert_same_bits(got, oracle.allreduce(x, G, threads=8), f"call {k}: against the oracle")
 
 
+def test_static_scratch_inside_a_graph():
+    """The callers this entry point is for: captured in a HIP graph (after one eager call on the
+    device) and replayed with fresh inputs, with an eager call of another shape between replays,
+    which uses the same array."""
+    P, G, n = 16, 4, 131072
+    x = ri.random_inputs(9200, P, n, "bf16")
+    want = oracle.allreduce(x, G, threads=8)
+    plan = rar.rar_plan(P, G, n, 0)
+    src = to_device(x)
+    bufs = [t.clone() for t in src]
+    ptrs = (ctypes.c_void_p * P)(*[b.data_ptr() for b in bufs])
+    print("[gpu] rar_allreduce_static inside a graph", flush=True)
+    assert rar.lib.rar_allreduce_static(ptrs, plan, torch.cuda.current_stream().cuda_stream) == 0   # eager first
+    torch.cuda.synchronize()
+    stream = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(stream):
+        with torch.cuda.graph(graph, stream=stream):
+            assert rar.lib.rar_allreduce_static(ptrs, plan, stream.cuda_stream) == 0
+    small = ri.random_inputs(9201, 8, 777, "f32")
+    for rep in range(3):
+        for b, s_ in zip(bufs, src):
+            b.copy_(s_)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert rar.rar_plan_status(plan, 0) == 0
+        assert_same_bits(to_host(bufs, x.dtype), want, f"replay {rep}")
+        assert_same_bits(through_static(small, 4, 1), oracle.allreduce(small, 4), f"eager call between replays {rep}")
+    rar.rar_plan_free(plan)
+
+
 def test_static_scratch_limit():
     w = ri.WORKLOADS["c4"]                 # 160 MiB of partial buffers: beyond the array
     plan = rar.rar_plan(w.P, w.G, w.n, 0)
