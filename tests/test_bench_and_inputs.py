@@ -29,6 +29,17 @@ def test_algorithmic_bytes_match_the_schedule():
         assert w.P * (reads + writes) == want
 
 
+def test_moved_bytes_are_what_the_fused_kernel_touches():
+    """Per rank: reads M (reduce-scatter) + L*M/G (one peer partial per step), writes L*M/G (its own
+    partial for every step but the last) + M (all-gather): never more than the schedule's count."""
+    sys.path.insert(0, ROOT)
+    import bench
+    for name, want in (("c1", 2621440), ("c2", 12582912), ("c3", 117440512), ("c4", 536870912)):
+        w = ri.WORKLOADS[name]
+        assert bench.moved_bytes(w.P, w.G, w.N, w.bytes_per_rank) == want
+        assert want < bench.algorithmic_bytes(w.P, w.G, w.N, w.bytes_per_rank)
+
+
 def test_workload_table():
     shapes = {"c1": (8, 4, 128 << 10), "c2": (16, 4, 256 << 10), "c3": (32, 4, 1 << 20), "c4": (64, 4, 2 << 20)}
     for name, (P, G, nbytes) in shapes.items():
