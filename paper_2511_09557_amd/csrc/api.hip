@@ -179,7 +179,11 @@ Ordering g_ordering[16];
 void wait_for_stream(Ordering &o, hipStream_t stream, hipStream_t other) {
     if (other == stream) return;
     unsigned long long mine = 0, theirs = 0;
-    const bool cap_mine = capturing(stream, &mine), cap_theirs = capturing(other, &theirs);
+    const bool cap_mine = capturing(stream, &mine);
+    // the legacy default stream cannot belong to a capture, and merely asking about it while a
+    // blocking stream is being captured would invalidate that capture
+    if (cap_mine && other == nullptr) return;
+    const bool cap_theirs = capturing(other, &theirs);
     // a dependency cannot cross the boundary of a capture: inside capture only streams of the same capture are ordered
     if (cap_mine != cap_theirs || (cap_mine && mine != theirs)) return;
     if (!o.event) return;

@@ -756,6 +756,75 @@ def test_two_default_plans_in_one_graph():
     a.close(), b.close()
 
 
+def test_two_host_threads_with_their_own_plans():
+    """Two host threads, each with its own plan, buffers and stream, launching at the same time:
+    the library's bookkeeping of fused launches per device is shared between them (a lock, an
+    event); every call of both threads must give the oracle's bits and no wait may time out."""
+    import threading
+    w = ri.WORKLOADS["c2"]
+    xs = [ri.make_inputs(w), np.ascontiguousarray(ri.make_inputs(w)[::-1])]
+    wants = [oracle.allreduce(x, w.G, threads=8) for x in xs]
+    errors = []
+
+    def worker(k):
+        try:
+            ar = rar.AllReduce(w.P, w.G, w.n, 0, MODES["auto" if k else "fused"])
+            rar.rar_plan_set_wait_limit_us(ar.plan, 2_000_000)
+            stream = torch.cuda.Stream()
+            src = to_device(xs[k])
+            bufs = [t.clone() for t in src]
+            ar.bind(bufs)
+            for it in range(100):
+                with torch.cuda.stream(stream):
+                    for b, s_ in zip(bufs, src):
+                        b.copy_(s_, non_blocking=True)
+                    ar.launch(stream)
+                if it % 10 == 9:
+                    assert ar.status(stream) == 0
+                    assert_same_bits(to_host(bufs, xs[k].dtype), wants[k], f"thread {k}, call {it}")
+            assert ar.status(stream) == 0
+            ar.close()
+        except Exception as e:                     # a thread's assertion must reach pytest
+            errors.append((k, repr(e)))
+
+    print("[gpu] two host threads", flush=True)
+    threads = [threading.Thread(target=worker, args=(k,)) for k in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join(timeout=120)
+    assert not any(t.is_alive() for t in threads), "a thread did not finish"
+    assert not errors, errors
+
+
+def test_plans_that_share_the_device_next_to_one_that_does_not():
+    """A plan with the default concurrency between two plans that were told they share the device
+    with one other: the exclusive launch waits for both sharing streams and the later sharing
+    launches wait for it; all three keep giving the oracle's bits."""
+    w = ri.WORKLOADS["c2"]
+    x = ri.make_inputs(w)
+    want = oracle.allreduce(x, w.G, threads=8)
+    plans = [rar.AllReduce(w.P, w.G, w.n, 0, 1) for _ in range(3)]
+    rar.rar_plan_set_concurrency(plans[0].plan, 2)
+    rar.rar_plan_set_concurrency(plans[2].plan, 2)
+    streams = [torch.cuda.Stream() for _ in range(3)]
+    print("[gpu] sharing and exclusive plans", flush=True)
+    for rep in range(5):
+        bufs = [to_device(x) for _ in range(3)]
+        for p, b in zip(plans, bufs):
+            p.bind(b)
+        torch.cuda.synchronize()
+        order = (0, 2, 1) if rep % 2 else (1, 0, 2)
+        for k in order:
+            plans[k].launch(streams[k])
+        torch.cuda.synchronize()
+        for k in range(3):
+            assert plans[k].status(streams[k]) == 0
+            assert_same_bits(to_host(bufs[k], x.dtype), want, f"rep {rep}, plan {k}")
+    for p in plans:
+        p.close()
+
+
 def test_measurement_aids():
     """rar_launch_floor, rar_barrier_only, rar_copy_probe and rar_read_probe do what the header says
     and leave the plan usable: the barrier-only kernel moves the flag counters like a real call."""
