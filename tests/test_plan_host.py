@@ -217,3 +217,59 @@ def test_no_device_gives_an_error_not_a_crash():
         rar.rar_allreduce([0x100000 + 4096 * i for i in range(8)], plan)
     assert e.value.status == -7
     rar.rar_plan_free(plan)
+
+
+def test_new_entry_points_without_a_device():
+    """The chained, static-scratch and probe entry points check their arguments on the host and then
+    fail with RAR_ERR_HIP where there is no device; nothing crashes."""
+    import ctypes
+    import torch
+    plan = rar.rar_plan(8, 4, 1024, 0)
+    ptrs = [0x100000 + 4096 * i for i in range(8)]
+    arr = (ctypes.c_void_p * 8)(*ptrs)
+    rar.rar_plan_set_scratch(plan, 0x1000, 1 << 30)
+    for K in (0, -3, (1 << 16) + 1):
+        assert binding.lib.rar_allreduce_chain(arr, plan, K, None) == -1
+    assert binding.lib.rar_allreduce_chain(None, plan, 2, None) == -1
+    assert binding.lib.rar_allreduce_static(None, plan, None) == -1
+    assert binding.lib.rar_read_probe(None, 0x1000, 1024, None) == -1
+    assert binding.lib.rar_read_probe(0x1000, 0x2000, 1000, None) == -6
+    big = rar.rar_plan(64, 4, 1048576, 0)
+    assert rar.rar_plan_static_bytes(big) > rar.RAR_STATIC_SCRATCH_BYTES
+    assert binding.lib.rar_allreduce_static((ctypes.c_void_p * 64)(*[0x100000 + 0x1000 * i for i in range(64)]), big, None) == -4
+    rar.rar_plan_free(big)
+    assert rar.rar_plan_static_bytes(plan) <= rar.rar_plan_scratch_bytes(plan)
+    if not torch.cuda.is_available():
+        assert binding.lib.rar_allreduce_chain(arr, plan, 2, None) == -7
+        assert binding.lib.rar_allreduce_static(arr, plan, None) == -7
+        assert binding.lib.rar_launch_floor(plan, None) == -7
+    rar.rar_plan_free(plan)
+
+
+def test_no_grid_beyond_four_workgroups_per_compute_unit():
+    """Whatever B_s is asked for, P * B_s stays within four workgroups per compute unit (256 compute
+    units until a device has been seen), also for the tuning of a chained launch's plan."""
+    for P, G, n in ((8, 4, 1 << 22), (16, 4, 1 << 22), (64, 4, 1 << 20), (128, 4, 1 << 21), (64, 8, 1 << 22), (128, 1, 1 << 20)):
+        plan = rar.rar_plan(P, G, n, 0)
+        for C_s in (4096, 8192, 16384, 32768, 0):
+            for B_s in (0, 1, 7, 64, 256):
+                rar.rar_plan_set_tuning(plan, B_s, C_s)
+                got_B, got_C = rar.rar_plan_get_tuning(plan)
+                assert P * got_B <= 4 * 256 or got_B == 1, (P, G, n, B_s, C_s, got_B)
+                assert C_s == 0 or got_C == C_s
+        rar.rar_plan_free(plan)
+
+
+def test_second_buffer_set_for_chained_calls():
+    """Plans with chunks of at most 256 KiB carry a second set of partial and data+flag buffers (the
+    odd calls of a chain); longer chunks do not."""
+    small = rar.rar_plan(16, 4, 131072, 0)          # 64 KiB chunks
+    L = rar.rar_plan_steps(small)
+    chunk = 65536
+    first_set = 256 + (L + 1) * 16 * 1024 + (L + 1) * 16 * chunk
+    assert rar.rar_plan_static_bytes(small) == first_set
+    assert rar.rar_plan_scratch_bytes(small) >= 2 * (L + 1) * 16 * chunk + 2 * L * 16 * 2 * chunk
+    rar.rar_plan_free(small)
+    big = rar.rar_plan(64, 4, 1048576, 0)
+    assert rar.rar_plan_scratch_bytes(big) == rar.rar_plan_static_bytes(big)
+    rar.rar_plan_free(big)
