@@ -322,9 +322,20 @@ def bench_workload(name: str, warmup: int, steps: int, extras: bool, mode: str =
             ar.launch(st)
         ar.set_mode(rar.RAR_MODE_AUTO)      # as a caller who sets nothing would run it
         both = time_graph(mm_then_ar, 100, 2, 10)
+        # the all-reduce alone between two events, launched eagerly right behind the product (its
+        # launch is queued while the product runs): the kernel's own duration plus the gap before it
+        brackets = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(40)]
+        for e0, e1 in brackets:
+            torch.bmm(a_sh, w_sh, out=whole)
+            e0.record()
+            ar.launch(cur)
+            e1.record()
+        torch.cuda.synchronize()
+        between = sorted(e0.elapsed_time(e1) * 1000.0 for e0, e1 in brackets[5:])
         ar.set_mode(rar.RAR_MODE_FUSED)
         out["graph100_matmul_us"] = mm
         out["graph100_interleaved_allreduce_us"] = both - mm
+        out["interleaved_between_events_us"] = between[len(between) // 2]
         del a_sh, w_sh, whole
         # the data+flag ("packed") exchange of Section 4.2.2, where the planner offers it
         try:
@@ -655,6 +666,30 @@ def cold_loop(workload: str, calls: int) -> None:
     ar.close()
 
 
+def interleaved_loop(workload: str, calls: int) -> None:
+    """For a profiler: `calls` x (every rank's row-parallel product written into its message,
+    all-reduce of the workload in automatic mode) launched eagerly, so that a kernel trace shows
+    the all-reduce kernel's own duration behind the compute that produces its input."""
+    import torch
+    import paper_2511_09557_amd as rar
+    import rar_inputs as ri
+    w = ri.WORKLOADS[workload]
+    bufs = device_bufs(ri.make_inputs(w))
+    ar = rar.AllReduce(w.P, w.G, w.n, rar.RAR_BF16, rar.RAR_MODE_AUTO)
+    ar.bind(bufs)
+    hidden = 8192 if w.bytes_per_rank <= (256 << 10) else 16384
+    tokens = max(w.n // hidden, 1)
+    whole = bufs[0]._base.view(w.P, tokens, hidden)
+    a_sh = torch.randn(w.P, tokens, hidden // w.P, device="cuda:0", dtype=torch.bfloat16)
+    w_sh = torch.randn(w.P, hidden // w.P, hidden, device="cuda:0", dtype=torch.bfloat16) / hidden ** 0.5
+    st = torch.cuda.current_stream().cuda_stream
+    for _ in range(calls):
+        torch.bmm(a_sh, w_sh, out=whole)
+        ar.launch(st)
+    assert ar.status() == 0
+    ar.close()
+
+
 def chain_loop(workload: str, launches: int, K: int = 100) -> None:
     """For a profiler: `launches` chained launches of K all-reduces each (rar_allreduce_chain), fused mode."""
     import torch
@@ -682,6 +717,7 @@ def main() -> int:
                     help="with --no-extras: run the headline workload in this mode (the JSON line says which)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--cold-loop", type=int, metavar="CALLS", help="for a profiler: only CALLS x (cache sweep, fused all-reduce of --workload)")
+    ap.add_argument("--interleaved-loop", type=int, metavar="CALLS", help="for a profiler: only CALLS x (row-parallel products, all-reduce of --workload in automatic mode)")
     ap.add_argument("--chain-loop", type=int, metavar="LAUNCHES", help="for a profiler: only LAUNCHES chains of 100 all-reduces of --workload (automatic mode)")
     ap.add_argument("--sensitivity", metavar="OUT.md", help="run the B_s x C_s sensitivity study instead and write it to this file")
     ap.add_argument("--hierarchy", metavar="OUT.md", help="run the flat-versus-hierarchical study instead and write it to this file")
@@ -712,6 +748,9 @@ def main() -> int:
     if args.cold_loop:
         cold_loop(args.workload, args.cold_loop)
         copy_probe()
+        return 0
+    if args.interleaved_loop:
+        interleaved_loop(args.workload, args.interleaved_loop)
         return 0
     if args.chain_loop:
         chain_loop(args.workload, args.chain_loop)
@@ -763,6 +802,14 @@ def main() -> int:
                             "graph_difference_method": "HIP graphs of 20 x (256 MiB copy, all-reduce) minus graphs of the copies alone",
                             "after_read_only_sweep_us": head["cold_after_read_sweep_us"],
                             "after_read_only_sweep_note": "graph difference with a 512 MiB read-only sweep instead of the copy"}
+        # behind the compute that produces its input (automatic mode, as a caller would run it)
+        inter, inter_diff = head["interleaved_between_events_us"], head["graph100_interleaved_allreduce_us"]
+        roofline["interleaved"] = {"us": inter, "GBps": moved / (inter * 1e-6) / 1e9, "frac": moved / (inter * 1e-6) / 1e9 / HBM_PEAK_GBPS,
+                                   "method": "every rank's row-parallel product (bf16, weights of hidden x hidden in total) written into its "
+                                             "message before every all-reduce; median of 35 eager pairs, HIP events around the all-reduce alone",
+                                   "graph_difference_us": inter_diff,
+                                   "graph_difference_frac": moved / (inter_diff * 1e-6) / 1e9 / HBM_PEAK_GBPS,
+                                   "graph_difference_method": "HIP graphs of 100 x (products, all-reduce) minus graphs of the products alone"}
         roofline["streaming_ceilings"] = streaming_ceilings()
     line = {
         "metric": "us per all-reduce at 128KB-2MB bf16 (P virtual ranks); achieved HBM GB/s vs peak",

@@ -188,7 +188,9 @@ int rar_plan_set_concurrency(rar_plan_t *plan, int k);
 /* Upper bound on the time one step-barrier wait may take before the kernel gives up, in
  * microseconds (default 5,000,000).  A wait that gives up records RAR_ERR_TIMEOUT in the
  * scratch header, and every workgroup still runs to the end of the kernel (no hang); the
- * output buffers are then unspecified. */
+ * output buffers are then unspecified.  The clock is looked at every 32 polls, so a wait that
+ * is satisfied within those never gives up.  0 is for tests of the time-out handling: a wait
+ * then gives up as soon as it has looked once without finding what it waits for. */
 int rar_plan_set_wait_limit_us(rar_plan_t *plan, uint64_t microseconds);
 
 /* Synchronise `stream`, then report whether a step-barrier wait of this plan has given up since
@@ -241,8 +243,13 @@ int rar_allreduce_chain(void *const *bufs, rar_plan_t *plan, int K, void *stream
  * RAR_ERR_LIMIT otherwise.  All calls on one GPU share the array: the call clears the header
  * and the flags with a fill kernel on `stream` before the all-reduce, so plans of any shape
  * may alternate, and calls that overlap in time on one GPU race (order them on one stream).
- * A wait that gives up is reported by the plan's next rar_plan_status (it reads the array's
- * header); since every call clears the flags, it does not affect later calls. */
+ * Like any fused launch of a plan with concurrency 1, the call is ordered behind the fused
+ * launches made on other streams.  A wait that gives up sets the status word in the array's
+ * header, which no call clears: until rar_plan_status has been asked, later calls on that GPU
+ * give up their waits at once (unspecified results).  rar_plan_status (of any plan that has
+ * run on the array since its last query) reports RAR_ERR_TIMEOUT if the word was set, by one
+ * of its own calls or by another plan's that ran on the array in the meantime, and clears it;
+ * the calls after that work again, since every call starts from cleared flags. */
 #define RAR_STATIC_SCRATCH_BYTES (48u << 20)
 int rar_allreduce_static(void *const *bufs, rar_plan_t *plan, void *stream);
 size_t rar_plan_static_bytes(const rar_plan_t *plan);

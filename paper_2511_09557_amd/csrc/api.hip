@@ -21,6 +21,10 @@ namespace {
 
 std::mutex g_static_guard;
 unsigned char *g_static_ptr[16];   // device address of `scratch` per device (each GPU has its own copy)
+// Time-outs found in a device's array so far (by rar_plan_status of whichever plan looked first):
+// the array's status word is shared by all plans, so a plan compares this count with the one it saw
+// at its first call since its last status query.
+unsigned long g_static_epoch[16];
 
 int static_scratch(int *device, unsigned char **out) {
     int dev = 0;
@@ -261,15 +265,20 @@ int rar_plan_status(rar_plan_t *plan, void *stream) {
     }
     if (plan->ran_static) {  // calls on the library's array report through its header alone
         unsigned char *array = nullptr;
-        int rc = static_scratch(nullptr, &array);
+        int device = 0;
+        int rc = static_scratch(&device, &array);
         if (rc != RAR_OK) return rc;
+        std::lock_guard<std::mutex> lock(g_static_guard);
         uint32_t word = 0;
         if (rar::note_hip(hipMemcpy(&word, array, sizeof word, hipMemcpyDeviceToHost)) != hipSuccess) return RAR_ERR_HIP;
         if (word != 0) {
-            timed_out = true;
+            ++g_static_epoch[device];
             word = 0;
             if (rar::note_hip(hipMemcpy(array, &word, sizeof word, hipMemcpyHostToDevice)) != hipSuccess) return RAR_ERR_HIP;
         }
+        // a time-out found since this plan's first call on the array, by this query or by another
+        // plan's: this plan's calls ran beside it on the same flags
+        timed_out = timed_out || g_static_epoch[device] != plan->static_epoch;
         plan->ran_static = false;
     }
     if (!timed_out) return RAR_OK;
@@ -364,11 +373,18 @@ int rar_allreduce_static(void *const *bufs, rar_plan_t *plan, void *stream) {
     rc = fused_tuning(plan, false, &t);
     if (rc != RAR_OK) return rc;
     hipStream_t st = as_stream(stream);
-    // whatever the last call on this GPU left behind: header and flags start at zero (a fill
-    // kernel, which a captured graph can replay; no pointer to host memory in the header)
-    rc = rar::launch_fill_zero(array, g.data_offset, nullptr, st);
+    if (!plan->ran_static) {
+        std::lock_guard<std::mutex> lock(g_static_guard);
+        plan->static_epoch = g_static_epoch[device];
+        plan->ran_static = true;
+    }
+    order_fused_launch(plan, st);  // behind fused launches of other streams, like any fused launch
+    // whatever the last call on this GPU left behind: the flags and the rest of the header start
+    // at zero (a fill kernel, which a captured graph can replay; no pointer to host memory in the
+    // header).  The status word in front stays as it is: a wait that gave up is not forgotten
+    // before rar_plan_status has reported it.
+    rc = rar::launch_fill_zero(array + 4, g.data_offset - 4, nullptr, st);
     if (rc != RAR_OK) return rc;
-    plan->ran_static = true;
     return rar::launch_fused(*plan, array, ptrs, t, true, 0, st);
 }
 

@@ -350,7 +350,7 @@ __device__ __forceinline__ void wait_for(const Shape &s, const u32 *flag, u32 ex
                 const u32 seen = __hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 if (static_cast<int>(seen - expect) >= 0) break;
                 __builtin_amdgcn_s_sleep(1);
-                if ((++spins & 31u) == 0u) {
+                if ((++spins & 31u) == 0u || s.wait_ticks == 0u) {  // a limit of 0: give up after the first look (tests)
                     const bool late = wall_clock64() - t0 > s.wait_ticks;
                     if (late) __hip_atomic_store(status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     if (late || __hip_atomic_load(status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) {
@@ -569,7 +569,7 @@ __device__ __forceinline__ void load_slice_packed(const Shape &s, const u64 *buf
         }
         if (__all(ready) || gave_up) break;
         __builtin_amdgcn_s_sleep(1);
-        if ((++spins & 31u) == 0u) {
+        if ((++spins & 31u) == 0u || s.wait_ticks == 0u) {  // a limit of 0: give up after the first look (tests)
             const bool late = wall_clock64() - t0 > s.wait_ticks;  // wave-uniform
             if (late) __hip_atomic_store(status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (late || __hip_atomic_load(status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) gave_up = true;

@@ -294,7 +294,7 @@ int rar_plan_set_concurrency(rar_plan_t *plan, int k) {
 }
 
 int rar_plan_set_wait_limit_us(rar_plan_t *plan, uint64_t microseconds) {
-    if (!plan || microseconds == 0) return RAR_ERR_ARG;
+    if (!plan) return RAR_ERR_ARG;
     plan->wait_limit_us = microseconds;
     return RAR_OK;
 }

@@ -76,6 +76,7 @@ struct rar_plan_s {
     int compute_units = 256;   // of the device the residency was measured on (MI355X until then)
     int device = -1;           // the device of the first launch
     bool ran_static = false;   // rar_allreduce_static has run on this plan (its time-outs sit in the library's array)
+    unsigned long static_epoch = 0;  // time-outs found in that array, by any plan, when this plan first ran on it
     // One word of pinned host memory that a kernel sets when a step-barrier wait gives up, so that
     // the next call can refuse to run without synchronising anything.  Allocated at the first
     // launch by the part of the library that may call HIP, released through `release_host_status`.

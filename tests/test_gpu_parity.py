@@ -459,10 +459,10 @@ def test_graph_replay(mode):
 
 
 def force_timeout(ar, bufs, calls=20):
-    """Launch with a 10 ns wait limit until a wait has given up (likely within a few calls, not
-    certain: a wait that is satisfied within 32 polls never looks at the clock).  Every kernel
-    still runs to its end.  Returns whether a time-out was reported; the plan is re-armed."""
-    rar.rar_plan_set_wait_limit_us(ar.plan, 1)
+    """Launch with a wait limit of 0 (a wait gives up as soon as it has looked once without finding
+    its flag or word) until a wait has given up.  Every kernel still runs to its end.  Returns
+    whether a time-out was reported; the plan is re-armed."""
+    rar.rar_plan_set_wait_limit_us(ar.plan, 0)
     seen = False
     try:
         for _ in range(calls):
@@ -483,7 +483,7 @@ def force_timeout(ar, bufs, calls=20):
 
 @pytest.mark.parametrize("mode", ["fused", "packed"])
 def test_wait_limit_ends_every_workgroup(mode):
-    """A 1-tick wait limit makes waits give up instead of spinning: the kernel must still
+    """A wait limit of 0 makes waits give up instead of spinning: the kernel must still
     finish, report the time-out, and the plan must work again afterwards."""
     w = ri.WORKLOADS["c3"]
     x = ri.make_inputs(w)
@@ -492,13 +492,12 @@ def test_wait_limit_ends_every_workgroup(mode):
     ar.set_tuning(2, 4096)                     # many trips, so some wait is certain to be pending
     bufs = to_device(x)
     print("[gpu] wait-limit run", flush=True)
-    timed_out = force_timeout(ar, bufs)
+    assert force_timeout(ar, bufs), "thousands of waits, and not one had to look twice?"
     assert ar.status() == 0                    # reported once, then clean
     bufs = to_device(x)
     ar(bufs)
     assert ar.status() == 0
     assert_same_bits(to_host(bufs, x.dtype), want, "after a time-out")
-    print(f"[gpu] wait-limit run: time-out seen = {timed_out}", flush=True)   # likely, not certain; recovery is what is checked
     ar.close()
 
 
@@ -512,7 +511,7 @@ def test_a_timed_out_plan_refuses_to_launch():
     ar.set_tuning(2, 4096)
     bufs = to_device(x)
     ar.bind(bufs)
-    rar.rar_plan_set_wait_limit_us(ar.plan, 1)
+    rar.rar_plan_set_wait_limit_us(ar.plan, 0)   # a wait gives up as soon as it has looked once in vain
     print("[gpu] poisoned plan", flush=True)
     refused = False
     for _ in range(30):
@@ -524,48 +523,51 @@ def test_a_timed_out_plan_refuses_to_launch():
             break
         torch.cuda.synchronize()               # the kernel has ended: its report, if any, is in host memory
     rar.rar_plan_set_wait_limit_us(ar.plan, 5_000_000)
-    if refused:
-        before = [b.clone() for b in bufs]
-        for call in (ar.launch, lambda: ar.launch_chain(2), ar.barrier_only):
-            with pytest.raises(rar.RarError) as e:
-                call()
-            assert e.value.status == -8
-        torch.cuda.synchronize()
-        for b, old in zip(bufs, before):       # nothing was enqueued
-            assert torch.equal(b.view(torch.int16), old.view(torch.int16))
-        assert ar.status() == -8
+    assert refused, "thousands of waits, and not one had to look twice?"
+    before = [b.clone() for b in bufs]
+    for call in (ar.launch, lambda: ar.launch_chain(2), ar.barrier_only):
+        with pytest.raises(rar.RarError) as e:
+            call()
+        assert e.value.status == -8
+    torch.cuda.synchronize()
+    for b, old in zip(bufs, before):           # nothing was enqueued
+        assert torch.equal(b.view(torch.int16), old.view(torch.int16))
+    assert ar.status() == -8
     assert ar.status() == 0
     bufs = to_device(x)
     ar(bufs)
     assert ar.status() == 0
     assert_same_bits(to_host(bufs, x.dtype), want, "after the report")
-    print(f"[gpu] poisoned plan: a launch was refused = {refused}", flush=True)
     ar.close()
 
 
-def test_autotune_discards_candidates_that_time_out():
-    """rar_autotune with a 10 ns wait limit: candidates during which a wait gave up do not count.
-    Either some candidate survives (then the plan must be clean and exact with the chosen pair),
-    or none does and the call says RAR_ERR_TIMEOUT; the plan works afterwards either way."""
+@pytest.mark.parametrize("limit_us", [0, 1])
+def test_autotune_discards_candidates_that_time_out(limit_us):
+    """rar_autotune under a wait limit that waits cannot keep: candidates during which a wait gave
+    up do not count.  With a limit of 0 (give up after the first look) none survives and the call
+    says RAR_ERR_TIMEOUT; with 1 us (the clock is looked at every 32 polls) some candidate may
+    survive, and the plan must then be clean and exact with the chosen pair.  The plan works
+    afterwards either way."""
     w = ri.WORKLOADS["c3"]
     x = ri.make_inputs(w)
     want = oracle.allreduce(x, w.G, threads=8)
     ar = rar.AllReduce(w.P, w.G, w.n, 0, 1)
-    rar.rar_plan_set_wait_limit_us(ar.plan, 1)
-    print("[gpu] autotune under a 10 ns wait limit", flush=True)
+    rar.rar_plan_set_wait_limit_us(ar.plan, limit_us)
+    print(f"[gpu] autotune under a wait limit of {limit_us} us", flush=True)
     try:
         ar.autotune(to_device(x), calls=5)
         outcome = "a candidate survived"
     except rar.RarError as e:
         assert e.status == -8
         outcome = "no candidate survived"
+    assert limit_us != 0 or outcome == "no candidate survived"
     rar.rar_plan_set_wait_limit_us(ar.plan, 5_000_000)
     assert ar.status() == 0                    # autotune leaves no time-out pending
     bufs = to_device(x)
     ar(bufs)
     assert ar.status() == 0
     assert_same_bits(to_host(bufs, x.dtype), want, outcome)
-    print(f"[gpu] autotune under a 10 ns wait limit: {outcome}", flush=True)
+    print(f"[gpu] autotune under a wait limit of {limit_us} us: {outcome}", flush=True)
     ar.close()
 
 

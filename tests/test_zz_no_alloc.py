@@ -98,3 +98,37 @@ def test_static_scratch_limit():
     ptrs = (ctypes.c_void_p * w.P)(*[b.data_ptr() for b in bufs])
     assert rar.lib.rar_allreduce_static(ptrs, plan, None) == -4
     rar.rar_plan_free(plan)
+
+
+def test_static_scratch_keeps_a_timeout_until_it_is_reported():
+    """The array's status word is shared by every plan on the GPU and no call clears it: a wait
+    that gave up (forced here from the host with a wait limit of 0: a wait gives up as soon as it
+    has looked once in vain; every kernel still runs to its end) is reported to the plan that caused it and to a plan that ran on the array before
+    the report, however many calls were made in between, and the calls after the report are
+    exact again."""
+    P, G, n = 32, 4, 524288
+    x = ri.random_inputs(9300, P, n, "bf16")
+    want = oracle.allreduce(x, G, threads=8)
+    st = torch.cuda.current_stream().cuda_stream
+    a, b = rar.rar_plan(P, G, n, 0), rar.rar_plan(P, G, n, 0)
+    rar.rar_plan_set_tuning(a, 2, 4096)                    # many trips, so some wait is all but certain to be pending
+    bufs = to_device(x)
+    ptrs = (ctypes.c_void_p * P)(*[t.data_ptr() for t in bufs])
+    print("[gpu] rar_allreduce_static with a wait limit of 0", flush=True)
+    rar.rar_plan_set_wait_limit_us(a, 0)
+    for _ in range(3):                                     # no status query in between
+        assert rar.lib.rar_allreduce_static(ptrs, a, st) == 0
+    rar.rar_plan_set_wait_limit_us(a, 5_000_000)
+    torch.cuda.synchronize()
+    assert rar.lib.rar_allreduce_static(ptrs, b, st) == 0  # another plan, before anyone has asked
+    first = rar.rar_plan_status(b, st)
+    second = rar.rar_plan_status(a, st)
+    assert first == -8 and second == -8                    # both ran beside the same status word
+    for plan in (a, b):                                    # reported once, then clean
+        for t, row in zip(bufs, x):
+            t.copy_(torch.from_numpy(row.view(np.int16)).view(torch.bfloat16))
+        assert rar.lib.rar_allreduce_static(ptrs, plan, st) == 0
+        assert rar.rar_plan_status(plan, st) == 0
+        assert_same_bits(to_host(bufs, x.dtype), want, "after the report")
+    rar.rar_plan_free(a)
+    rar.rar_plan_free(b)
